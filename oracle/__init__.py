@@ -1,0 +1,150 @@
+"""ctypes front end of the CPU oracle (test infrastructure only).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this package.  It
+compiles ``orthrus_oracle.c`` with gcc on first use (plain -O2, no fast-math, OpenMP over
+independent outputs) and exposes the two oracle entry points on numpy arrays.  It imports
+nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "orthrus_oracle.c")
+_LIB = os.path.join(_HERE, "liborthrus_oracle.so")
+
+VIEW_DIFFUSION = 0
+VIEW_AR_VERIFY = 1
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle's C source into a shared library next to it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", tmp, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i32, i64, f64 = ctypes.c_int, ctypes.c_int64, ctypes.c_double
+        p = ctypes.c_void_p
+        lib.orthrus_oracle_num_threads.restype = ctypes.c_int
+        lib.orthrus_oracle_dual_view_attn.restype = ctypes.c_int
+        lib.orthrus_oracle_dual_view_attn.argtypes = [
+            i32, i32, i32, i32, i32, i32, i32, i64, i32, f64,
+            p, p, p, p, p, i64, i64, i64, p, p, p, p]
+        lib.orthrus_oracle_consensus_commit.restype = ctypes.c_int
+        lib.orthrus_oracle_consensus_commit.argtypes = [
+            i32, i32, i32, i32, i32, i32, i32, i32, i64,
+            p, p, p, p, p, p, i64, i64, i64, i64, p, p, p, p, p, p]
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().orthrus_oracle_num_threads())
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(a: np.ndarray, dtype, name: str) -> np.ndarray:
+    if a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError("%s must be a C-contiguous %s array" % (name, np.dtype(dtype).name))
+    return a
+
+
+def _pool_strides(pool: np.ndarray):
+    """Element strides (page, head, token) of a [pages, H_kv, P, d] pool."""
+    if pool.ndim != 4:
+        raise ValueError("pool must be [pages, H_kv, P, d]")
+    es = pool.itemsize
+    return pool.strides[0] // es, pool.strides[1] // es, pool.strides[2] // es
+
+
+def dual_view_attn(view: int, sm_scale: float, q: np.ndarray, k_blk: np.ndarray, v_blk: np.ndarray,
+                   k_pool: np.ndarray, v_pool: np.ndarray, page_table: np.ndarray,
+                   seq_lens: np.ndarray, want_lse: bool = False):
+    """Eq. 4 of the paper on bf16-bit inputs; returns fp64 ``out[B,K,H_q,d]`` (and ``lse[B,H_q,K]``)."""
+    lib = _load()
+    B, K, Hq, d = q.shape
+    Hkv = k_blk.shape[2]
+    _check(q, np.uint16, "q"); _check(k_blk, np.uint16, "k_blk"); _check(v_blk, np.uint16, "v_blk")
+    _check(k_pool, np.uint16, "k_pool"); _check(v_pool, np.uint16, "v_pool")
+    _check(page_table, np.int32, "page_table"); _check(seq_lens, np.int32, "seq_lens")
+    if k_blk.shape != (B, K, Hkv, d) or v_blk.shape != k_blk.shape:
+        raise ValueError("block K/V shape mismatch")
+    if k_pool.shape != v_pool.shape or k_pool.shape[1] != Hkv or k_pool.shape[3] != d:
+        raise ValueError("pool shape mismatch")
+    sp, sh, st = _pool_strides(k_pool)
+    out = np.empty((B, K, Hq, d), dtype=np.float64)
+    lse = np.empty((B, Hq, K), dtype=np.float64) if want_lse else None
+    rc = lib.orthrus_oracle_dual_view_attn(
+        B, Hq, Hkv, d, K, k_pool.shape[2], page_table.shape[1], k_pool.shape[0], int(view),
+        float(sm_scale), _ptr(q), _ptr(k_blk), _ptr(v_blk), _ptr(k_pool), _ptr(v_pool),
+        sp, sh, st, _ptr(page_table), _ptr(seq_lens), _ptr(out), _ptr(lse))
+    if rc != 0:
+        raise RuntimeError("orthrus_oracle_dual_view_attn failed with status %d" % rc)
+    return (out, lse) if want_lse else out
+
+
+def consensus_commit(ar_logits: np.ndarray, draft_tokens: np.ndarray,
+                     k_blk_ar: Optional[np.ndarray] = None, v_blk_ar: Optional[np.ndarray] = None,
+                     k_pool: Optional[np.ndarray] = None, v_pool: Optional[np.ndarray] = None,
+                     page_table: Optional[np.ndarray] = None, seq_lens: Optional[np.ndarray] = None,
+                     allow_capacity_error: bool = False) -> Dict[str, np.ndarray]:
+    """Eq. 8 consensus plus in-place commit.
+
+    ``k_blk_ar``/``v_blk_ar`` are ``[layers,B,K,H_kv,d]`` (or ``[B,K,H_kv,d]`` for one layer);
+    pools are ``[layers,pages,H_kv,P,d]`` or ``[pages,H_kv,P,d]``; both pools and ``seq_lens``
+    are updated in place.  With the K/V arguments omitted only the consensus outputs are made.
+    """
+    lib = _load()
+    B, K, V = ar_logits.shape
+    _check(ar_logits, np.float32, "ar_logits"); _check(draft_tokens, np.int32, "draft_tokens")
+    accept_len = np.empty(B, np.int32); num_committed = np.empty(B, np.int32)
+    out_tokens = np.empty((B, K), np.int32); next_anchor = np.empty(B, np.int32)
+    if k_blk_ar is None:
+        rc = lib.orthrus_oracle_consensus_commit(
+            B, K, V, 0, 0, 0, 0, 0, 0, _ptr(ar_logits), _ptr(draft_tokens), None, None, None, None,
+            0, 0, 0, 0, None, None, _ptr(accept_len), _ptr(num_committed), _ptr(out_tokens),
+            _ptr(next_anchor))
+    else:
+        kb = k_blk_ar if k_blk_ar.ndim == 5 else k_blk_ar[None]
+        vb = v_blk_ar if v_blk_ar.ndim == 5 else v_blk_ar[None]
+        kp = k_pool if k_pool.ndim == 5 else k_pool[None]
+        vp = v_pool if v_pool.ndim == 5 else v_pool[None]
+        for a, n in ((kb, "k_blk_ar"), (vb, "v_blk_ar"), (kp, "k_pool"), (vp, "v_pool")):
+            _check(a, np.uint16, n)
+        _check(page_table, np.int32, "page_table"); _check(seq_lens, np.int32, "seq_lens")
+        layers, _, _, Hkv, d = kb.shape
+        if kb.shape != (layers, B, K, Hkv, d) or vb.shape != kb.shape:
+            raise ValueError("block K/V shape mismatch")
+        if kp.shape != vp.shape or kp.shape[0] != layers or kp.shape[2] != Hkv or kp.shape[4] != d:
+            raise ValueError("pool shape mismatch")
+        es = kp.itemsize
+        sl, sp, sh, st = (kp.strides[0] // es, kp.strides[1] // es, kp.strides[2] // es,
+                          kp.strides[3] // es)
+        rc = lib.orthrus_oracle_consensus_commit(
+            B, K, V, layers, Hkv, d, kp.shape[3], page_table.shape[1], kp.shape[1],
+            _ptr(ar_logits), _ptr(draft_tokens), _ptr(kb), _ptr(vb), _ptr(kp), _ptr(vp),
+            sl, sp, sh, st, _ptr(page_table), _ptr(seq_lens), _ptr(accept_len),
+            _ptr(num_committed), _ptr(out_tokens), _ptr(next_anchor))
+    if rc != 0 and not (rc == -4 and allow_capacity_error):
+        raise RuntimeError("orthrus_oracle_consensus_commit failed with status %d" % rc)
+    return dict(accept_len=accept_len, num_committed=num_committed, out_tokens=out_tokens,
+                next_anchor=next_anchor, status=rc)
