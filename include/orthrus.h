@@ -1,0 +1,176 @@
+/*
+ * orthrus.h — C ABI of the MI355X (gfx950) library for the hot path of the Orthrus
+ * dual-view decode step: block attention of the diffusion view and of the AR verification
+ * view over one shared paged KV cache, greedy consensus, and in-place commit of the accepted
+ * tokens' K/V.
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers marked [dev] are DEVICE pointers owned by the caller (for instance torch
+ *     allocations); pointers marked [host] are host pointers.  The library never frees a
+ *     caller's pointer and never keeps one after the call returns.
+ *   - The compute entry points are asynchronous on the caller's HIP stream (`stream` is a
+ *     hipStream_t passed as void*; NULL = the default stream), do not synchronise with the
+ *     host and do not allocate.  Sequence lengths live on the device and are read by the
+ *     kernels, so consecutive decode steps can be queued without a host round trip.
+ *   - Every function returns an orthrus_status.  Argument errors are found on the host before
+ *     anything is launched; on such an error nothing has been written.
+ *   - Layouts are row-major with the last index contiguous.  bf16 means the upper 16 bits of
+ *     an IEEE fp32 value.
+ *   - Indices are 0-based: draft_tokens[b][k] is the paper's y-hat_{k+1}.
+ */
+#ifndef ORTHRUS_H
+#define ORTHRUS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct orthrus_ctx orthrus_ctx; /* opaque: device id, cached device properties, a device error word */
+
+typedef enum {
+    ORTHRUS_OK = 0,
+    ORTHRUS_EINVAL = -1,       /* NULL pointer, non-positive size, inconsistent shape */
+    ORTHRUS_EUNSUPPORTED = -2, /* legal shape outside what the kernels are built for (see orthrus_params) */
+    ORTHRUS_EWORKSPACE = -3,   /* workspace missing, misaligned or smaller than the *_workspace_bytes value */
+    ORTHRUS_ECAPACITY = -4,    /* device side: a needed page was not mapped (reported by orthrus_last_device_error) */
+    ORTHRUS_EHIP = -5          /* a HIP runtime call failed */
+} orthrus_status;
+
+typedef enum {
+    ORTHRUS_VIEW_DIFFUSION = 0, /* in-block keys visible to every block row (bidirectional) */
+    ORTHRUS_VIEW_AR_VERIFY = 1  /* in-block keys causal: row i sees in-block rows 0..i */
+} orthrus_view;
+
+/*
+ * Problem description shared by all entry points (plain data, filled by the caller).
+ *
+ * Supported by the kernels: head_dim in {64, 128}; page_size a power of two >= 16;
+ * 1 <= block_k <= 32; num_q_heads a multiple of num_kv_heads with
+ * (num_q_heads / num_kv_heads) * block_k <= 256; sm_scale > 0; every pool stride a multiple
+ * of 8 elements (16-byte rows).  Anything else that is otherwise consistent returns
+ * ORTHRUS_EUNSUPPORTED.
+ */
+typedef struct {
+    int32_t batch;             /* B: sequences in the step */
+    int32_t num_q_heads;       /* H_q */
+    int32_t num_kv_heads;      /* H_kv; query head h reads KV head h / (H_q / H_kv) */
+    int32_t head_dim;          /* d */
+    int32_t block_k;           /* K: positions in the block (anchor + K-1 drafts) */
+    int32_t page_size;         /* P: tokens per cache page */
+    int32_t max_pages_per_seq; /* row length of page_table */
+    int32_t max_seq_len;       /* HOST upper bound on every seq_lens[b] during the call (sizes the grid) */
+    int32_t num_splits;        /* attention: KV splits per (sequence, KV head); 0 = library chooses */
+    int32_t num_layers;        /* commit: layers written per call (block K/V and pools carry a layer axis) */
+    int32_t vocab;             /* consensus: V */
+    float sm_scale;            /* score scale of Eq. 4, normally 1/sqrt(d) */
+    int64_t num_pages;         /* pages in each pool; page ids outside [0, num_pages) count as unmapped */
+    /* element strides of k_pool / v_pool (both pools share them):
+       element (layer, page, kv head g, slot s, c) is at
+       layer*pool_stride_layer + page*pool_stride_page + g*pool_stride_head + s*pool_stride_tok + c */
+    int64_t pool_stride_layer;
+    int64_t pool_stride_page;
+    int64_t pool_stride_head;
+    int64_t pool_stride_tok;
+} orthrus_params;
+
+/* Creates a context on HIP device `device` (allocates one small device error word).  [host] out. */
+orthrus_status orthrus_create(orthrus_ctx **out, int device);
+/* Frees the context.  The caller must have synchronised every stream that used it. */
+orthrus_status orthrus_destroy(orthrus_ctx *ctx);
+/* Static description of a status code (never NULL). */
+const char *orthrus_status_string(orthrus_status s);
+
+/*
+ * Workspace sizes in bytes for the given params (0 is a valid answer).  Workspaces are
+ * [dev], 256-byte aligned, owned by the caller, and may be reused by the next call on the
+ * same stream.  A negative return is an orthrus_status.
+ */
+int64_t orthrus_attn_workspace_bytes(const orthrus_params *p);
+int64_t orthrus_consensus_workspace_bytes(const orthrus_params *p);
+/* Number of KV splits the attention call will use for these params (>= 1), or a negative status. */
+int32_t orthrus_attn_num_splits(const orthrus_params *p);
+
+/*
+ * Block attention of one view over the shared cache — Section 3.1, Eq. 4 of the paper:
+ *   O = Softmax(Q [K_AR || K_blk]^T * sm_scale) [V_AR || V_blk]
+ * for every sequence b, block row i < K and query head h.  The key axis is the sequence's
+ * cached tokens 0..seq_lens[b]-1 (the cache built by the AR view, Section 3.3: tokens before
+ * the anchor) followed by the block's own K rows.  In-block visibility depends on `view`:
+ * ORTHRUS_VIEW_DIFFUSION lets every row see all K in-block keys (Section 3.2, rule (ii) of
+ * the block mask, Eq. 6 second term); ORTHRUS_VIEW_AR_VERIFY is causal inside the block
+ * (Section 3.2 "standard causal masking"; Section 3.3, verification pass).  The cache is
+ * read-only here and is the same for both views.
+ *
+ *   q        [dev] bf16 [B, K, H_q, d]      queries of the block (post-projection, post-RoPE)
+ *   k_blk    [dev] bf16 [B, K, H_kv, d]     the block's own keys for this view
+ *   v_blk    [dev] bf16 [B, K, H_kv, d]     the block's own values for this view
+ *   k_pool   [dev] bf16 paged cache, strides in params (layer 0 is used)
+ *   v_pool   [dev] bf16 same strides
+ *   page_table [dev] int32 [B, max_pages_per_seq]; entry j maps tokens j*P .. j*P+P-1
+ *   seq_lens [dev] int32 [B]; 0 <= seq_lens[b] <= max_seq_len
+ *   out      [dev] bf16 [B, K, H_q, d]      written
+ *   lse      [dev] fp32 [B, H_q, K] or NULL natural-log sum of exp(scaled scores), written if given
+ *   workspace/workspace_bytes: at least orthrus_attn_workspace_bytes(p)
+ *
+ * Arithmetic: bf16 inputs, fp32 scores/softmax/accumulation, probabilities rounded to bf16
+ * for the value product, bf16 output.
+ * Device-side errors: a page id outside [0, num_pages) for a token below seq_lens[b], or
+ * seq_lens[b] outside [0, max_seq_len], sets the context's error word (ORTHRUS_ECAPACITY);
+ * the affected tokens are treated as absent, nothing is read out of bounds.
+ */
+orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p, orthrus_view view,
+                                      const void *q, const void *k_blk, const void *v_blk,
+                                      const void *k_pool, const void *v_pool,
+                                      const int32_t *page_table, const int32_t *seq_lens,
+                                      void *out, float *lse,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Greedy consensus and commit — Section 3.3 "Architectural Consensus Mechanism", Eq. 8, and
+ * Fig. 2(b): a draft is kept iff it equals the AR view's greedy token, left to right;
+ * verification stops at the first divergence, the AR token there is emitted as the
+ * correction, and only the K/V of the tokens now in the sequence is appended to the cache.
+ * Per sequence b (L = seq_lens[b] on entry):
+ *   am[k]  = argmax_v ar_logits[b][k][v]  (smallest index on ties; NaN ranks above all numbers)
+ *   accept_len[b]    = number of leading k with draft_tokens[b][k] == am[k]          (0..K)
+ *   num_committed[b] = m = min(accept_len[b] + 1, K)                                  (1..K)
+ *   out_tokens[b][0..m-1] = am[0..m-1], out_tokens[b][m..K-1] = -1, next_anchor[b] = am[m-1]
+ *   rows 0..m-1 of k_blk_ar / v_blk_ar (the AR view's K/V of the anchor and the accepted
+ *   drafts) are copied to token positions L..L+m-1 of every layer's pool; seq_lens[b] = L+m.
+ *
+ *   ar_logits    [dev] fp32 [B, K, V]      row k is conditioned on the anchor and drafts 0..k-1
+ *   draft_tokens [dev] int32 [B, K]        values outside [0, V) never match
+ *   k_blk_ar, v_blk_ar [dev] bf16 [num_layers, B, K, H_kv, d], or both NULL: consensus only
+ *                                           (pools, page_table and seq_lens are then not touched)
+ *   k_pool, v_pool [dev] bf16, updated in place; page_table [dev] as above
+ *   seq_lens     [dev] int32 [B], updated in place
+ *   accept_len, num_committed, next_anchor [dev] int32 [B]; out_tokens [dev] int32 [B, K]
+ *   workspace/workspace_bytes: at least orthrus_consensus_workspace_bytes(p)
+ *
+ * Device-side errors: if a position L..L+m-1 is not mapped (beyond max_pages_per_seq or page
+ * id outside [0, num_pages)) the sequence's pools and length are left untouched,
+ * num_committed[b] is 0 and the context's error word is set (ORTHRUS_ECAPACITY).
+ * Integer and byte results are exact.
+ */
+orthrus_status orthrus_consensus_commit(orthrus_ctx *ctx, const orthrus_params *p,
+                                        const float *ar_logits, const int32_t *draft_tokens,
+                                        const void *k_blk_ar, const void *v_blk_ar,
+                                        void *k_pool, void *v_pool,
+                                        const int32_t *page_table, int32_t *seq_lens,
+                                        int32_t *accept_len, int32_t *num_committed,
+                                        int32_t *out_tokens, int32_t *next_anchor,
+                                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Synchronises `stream`, copies the context's device error word to *code [host] (ORTHRUS_OK or
+ * ORTHRUS_ECAPACITY) and clears it.  This is the only entry point that blocks.
+ */
+orthrus_status orthrus_last_device_error(orthrus_ctx *ctx, void *stream, int32_t *code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ORTHRUS_H */

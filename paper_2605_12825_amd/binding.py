@@ -1,0 +1,195 @@
+"""Thin ctypes binding of liborthrus.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; nothing here computes.  Device
+buffers are torch tensors (torch is used for device memory and streams only); the functions
+pass their data pointers straight through.  There is no CPU fallback: if the library cannot be
+loaded the import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+from . import build as _build
+
+ORTHRUS_OK = 0
+ORTHRUS_EINVAL = -1
+ORTHRUS_EUNSUPPORTED = -2
+ORTHRUS_EWORKSPACE = -3
+ORTHRUS_ECAPACITY = -4
+ORTHRUS_EHIP = -5
+
+ORTHRUS_VIEW_DIFFUSION = 0
+ORTHRUS_VIEW_AR_VERIFY = 1
+
+EXPORTED = [
+    "orthrus_create", "orthrus_destroy", "orthrus_status_string", "orthrus_attn_workspace_bytes",
+    "orthrus_consensus_workspace_bytes", "orthrus_attn_num_splits", "orthrus_dual_view_attn",
+    "orthrus_consensus_commit", "orthrus_last_device_error",
+]
+
+
+class orthrus_params(ctypes.Structure):
+    """Mirror of the C struct orthrus_params."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("block_k", ctypes.c_int32), ("page_size", ctypes.c_int32),
+        ("max_pages_per_seq", ctypes.c_int32), ("max_seq_len", ctypes.c_int32),
+        ("num_splits", ctypes.c_int32), ("num_layers", ctypes.c_int32), ("vocab", ctypes.c_int32),
+        ("sm_scale", ctypes.c_float), ("num_pages", ctypes.c_int64),
+        ("pool_stride_layer", ctypes.c_int64), ("pool_stride_page", ctypes.c_int64),
+        ("pool_stride_head", ctypes.c_int64), ("pool_stride_tok", ctypes.c_int64),
+    ]
+
+
+class OrthrusError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, orthrus_status_string(status), status))
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_build.LIB):
+        # nothing built yet: build once; a stale library is the caller's to rebuild
+        _build.build_library()
+    lib = ctypes.CDLL(_build.LIB)
+    vp, i32p = ctypes.c_void_p, ctypes.c_void_p
+    pp = ctypes.POINTER(orthrus_params)
+    lib.orthrus_create.restype = ctypes.c_int
+    lib.orthrus_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
+    lib.orthrus_destroy.restype = ctypes.c_int
+    lib.orthrus_destroy.argtypes = [vp]
+    lib.orthrus_status_string.restype = ctypes.c_char_p
+    lib.orthrus_status_string.argtypes = [ctypes.c_int]
+    lib.orthrus_attn_workspace_bytes.restype = ctypes.c_int64
+    lib.orthrus_attn_workspace_bytes.argtypes = [pp]
+    lib.orthrus_consensus_workspace_bytes.restype = ctypes.c_int64
+    lib.orthrus_consensus_workspace_bytes.argtypes = [pp]
+    lib.orthrus_attn_num_splits.restype = ctypes.c_int32
+    lib.orthrus_attn_num_splits.argtypes = [pp]
+    lib.orthrus_dual_view_attn.restype = ctypes.c_int
+    lib.orthrus_dual_view_attn.argtypes = [vp, pp, ctypes.c_int, vp, vp, vp, vp, vp, i32p, i32p, vp, vp, vp,
+                                           ctypes.c_size_t, vp]
+    lib.orthrus_consensus_commit.restype = ctypes.c_int
+    lib.orthrus_consensus_commit.argtypes = [vp, pp, vp, i32p, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, i32p,
+                                             vp, ctypes.c_size_t, vp]
+    lib.orthrus_last_device_error.restype = ctypes.c_int
+    lib.orthrus_last_device_error.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+    return lib
+
+
+_lib = _load()
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a torch tensor, an int address, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else int(t.numel() * t.element_size())
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)
+
+
+def orthrus_status_string(status: int) -> str:
+    return _lib.orthrus_status_string(int(status)).decode()
+
+
+def orthrus_create(device: int = 0) -> int:
+    h = ctypes.c_void_p()
+    st = _lib.orthrus_create(ctypes.byref(h), int(device))
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_create")
+    return h.value
+
+
+def orthrus_destroy(ctx: int) -> None:
+    st = _lib.orthrus_destroy(ctx)
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_destroy")
+
+
+def orthrus_attn_workspace_bytes(p: orthrus_params) -> int:
+    n = _lib.orthrus_attn_workspace_bytes(ctypes.byref(p))
+    if n < 0:
+        raise OrthrusError(int(n), "orthrus_attn_workspace_bytes")
+    return int(n)
+
+
+def orthrus_consensus_workspace_bytes(p: orthrus_params) -> int:
+    n = _lib.orthrus_consensus_workspace_bytes(ctypes.byref(p))
+    if n < 0:
+        raise OrthrusError(int(n), "orthrus_consensus_workspace_bytes")
+    return int(n)
+
+
+def orthrus_attn_num_splits(p: orthrus_params) -> int:
+    n = _lib.orthrus_attn_num_splits(ctypes.byref(p))
+    if n < 0:
+        raise OrthrusError(int(n), "orthrus_attn_num_splits")
+    return int(n)
+
+
+def orthrus_dual_view_attn(ctx, p: orthrus_params, view: int, q, k_blk, v_blk, k_pool, v_pool, page_table,
+                           seq_lens, out, lse=None, workspace=None, stream=None, check: bool = True) -> int:
+    st = _lib.orthrus_dual_view_attn(ctx, ctypes.byref(p), int(view), _ptr(q), _ptr(k_blk), _ptr(v_blk),
+                                     _ptr(k_pool), _ptr(v_pool), _ptr(page_table), _ptr(seq_lens), _ptr(out),
+                                     _ptr(lse), _ptr(workspace), _nbytes(workspace), _stream_handle(stream))
+    if check and st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_dual_view_attn")
+    return st
+
+
+def orthrus_consensus_commit(ctx, p: orthrus_params, ar_logits, draft_tokens, k_blk_ar, v_blk_ar, k_pool, v_pool,
+                             page_table, seq_lens, accept_len, num_committed, out_tokens, next_anchor,
+                             workspace=None, stream=None, check: bool = True) -> int:
+    st = _lib.orthrus_consensus_commit(ctx, ctypes.byref(p), _ptr(ar_logits), _ptr(draft_tokens), _ptr(k_blk_ar),
+                                       _ptr(v_blk_ar), _ptr(k_pool), _ptr(v_pool), _ptr(page_table),
+                                       _ptr(seq_lens), _ptr(accept_len), _ptr(num_committed), _ptr(out_tokens),
+                                       _ptr(next_anchor), _ptr(workspace), _nbytes(workspace),
+                                       _stream_handle(stream))
+    if check and st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_consensus_commit")
+    return st
+
+
+def orthrus_last_device_error(ctx, stream=None) -> int:
+    code = ctypes.c_int32(0)
+    st = _lib.orthrus_last_device_error(ctx, _stream_handle(stream), ctypes.byref(code))
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_last_device_error")
+    return int(code.value)
+
+
+def make_params(*, batch, num_q_heads, num_kv_heads, head_dim, block_k, page_size, max_pages_per_seq, max_seq_len,
+                num_pages, num_splits=0, num_layers=1, vocab=0, sm_scale=None, pool_stride_layer=None,
+                pool_stride_page=None, pool_stride_head=None, pool_stride_tok=None) -> orthrus_params:
+    """Fills orthrus_params; pool strides default to the [pages, H_kv, P, d] layout."""
+    p = orthrus_params()
+    p.batch, p.num_q_heads, p.num_kv_heads, p.head_dim = batch, num_q_heads, num_kv_heads, head_dim
+    p.block_k, p.page_size, p.max_pages_per_seq, p.max_seq_len = block_k, page_size, max_pages_per_seq, max_seq_len
+    p.num_splits, p.num_layers, p.vocab = num_splits, num_layers, vocab
+    p.sm_scale = float(sm_scale) if sm_scale is not None else (1.0 / float(head_dim) ** 0.5 if head_dim > 0 else 0.0)
+    p.num_pages = num_pages
+    p.pool_stride_tok = head_dim if pool_stride_tok is None else pool_stride_tok
+    p.pool_stride_head = page_size * head_dim if pool_stride_head is None else pool_stride_head
+    p.pool_stride_page = num_kv_heads * page_size * head_dim if pool_stride_page is None else pool_stride_page
+    p.pool_stride_layer = num_pages * p.pool_stride_page if pool_stride_layer is None else pool_stride_layer
+    return p

@@ -1,0 +1,262 @@
+// Host side of the C ABI declared in orthrus.h: argument validation, launch planning and
+// workspace carving.  Nothing here computes; every step of the path runs in the kernels.
+#include "../../include/orthrus.h"
+#include "orthrus_internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+struct orthrus_ctx {
+    int device;
+    int num_cus;
+    int32_t *err_word;  // device
+};
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int log2_exact(int x)
+{
+    if (x <= 0 || (x & (x - 1))) return -1;
+    int s = 0;
+    while ((1 << s) < x) ++s;
+    return s;
+}
+
+// Checks shared by every entry point.  `need_attn` / `need_consensus` select the field groups.
+orthrus_status check_params(const orthrus_params *p, bool need_attn, bool need_consensus, bool need_pool)
+{
+    if (!p) return ORTHRUS_EINVAL;
+    if (p->batch < 0 || p->block_k <= 0) return ORTHRUS_EINVAL;
+    if (p->batch > 65535) return ORTHRUS_EUNSUPPORTED;
+    if (need_attn || need_pool) {
+        if (p->num_kv_heads <= 0 || p->head_dim <= 0 || p->page_size <= 0 || p->max_pages_per_seq <= 0 ||
+            p->num_pages <= 0)
+            return ORTHRUS_EINVAL;
+        if (p->pool_stride_page <= 0 || p->pool_stride_head <= 0 || p->pool_stride_tok <= 0) return ORTHRUS_EINVAL;
+        if (p->head_dim != 64 && p->head_dim != 128) return ORTHRUS_EUNSUPPORTED;
+        if (log2_exact(p->page_size) < 4) return ORTHRUS_EUNSUPPORTED;
+        if (p->num_kv_heads > 65535) return ORTHRUS_EUNSUPPORTED;
+        if ((p->pool_stride_page | p->pool_stride_head | p->pool_stride_tok | p->pool_stride_layer) & 7)
+            return ORTHRUS_EUNSUPPORTED;
+        if (p->pool_stride_tok < p->head_dim) return ORTHRUS_EINVAL;
+    }
+    if (p->block_k > 32) return ORTHRUS_EUNSUPPORTED;
+    if (need_attn) {
+        if (p->num_q_heads <= 0 || p->num_q_heads % p->num_kv_heads != 0) return ORTHRUS_EINVAL;
+        if (p->max_seq_len < 0 || p->num_splits < 0) return ORTHRUS_EINVAL;
+        if ((int64_t)p->max_seq_len > (int64_t)p->max_pages_per_seq * p->page_size) return ORTHRUS_EINVAL;
+        if (!(p->sm_scale > 0.f) || !std::isfinite(p->sm_scale)) return ORTHRUS_EINVAL;
+        if ((int64_t)(p->num_q_heads / p->num_kv_heads) * p->block_k > 256) return ORTHRUS_EUNSUPPORTED;
+    }
+    if (need_consensus) {
+        if (p->vocab <= 0) return ORTHRUS_EINVAL;
+    }
+    return ORTHRUS_OK;
+}
+
+orthrus_status make_plan(const orthrus_params *p, int num_cus, orthrus::AttnPlan *plan)
+{
+    orthrus::plan_attn(p->head_dim, p->num_q_heads / p->num_kv_heads, p->block_k, p->batch, p->num_kv_heads,
+                       p->max_seq_len, p->num_splits, num_cus, plan);
+    if (plan->num_splits > 65535 * 16) return ORTHRUS_EUNSUPPORTED;
+    return ORTHRUS_OK;
+}
+
+int consensus_chunks(const orthrus_params *p)
+{
+    const int ce = orthrus::consensus_chunk_elems();
+    return (p->vocab + ce - 1) / ce;
+}
+
+constexpr int kDefaultCUs = 256;  // MI355X; only used when sizing without a context
+
+}  // namespace
+
+extern "C" {
+
+const char *orthrus_status_string(orthrus_status s)
+{
+    switch (s) {
+    case ORTHRUS_OK: return "ok";
+    case ORTHRUS_EINVAL: return "invalid argument";
+    case ORTHRUS_EUNSUPPORTED: return "shape not supported by the gfx950 kernels";
+    case ORTHRUS_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case ORTHRUS_ECAPACITY: return "a needed cache page is not mapped";
+    case ORTHRUS_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+orthrus_status orthrus_create(orthrus_ctx **out, int device)
+{
+    if (!out) return ORTHRUS_EINVAL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return ORTHRUS_EHIP;
+    if (hipSetDevice(device) != hipSuccess) return ORTHRUS_EHIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return ORTHRUS_EHIP;
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return ORTHRUS_EUNSUPPORTED;
+    orthrus_ctx *c = new (std::nothrow) orthrus_ctx;
+    if (!c) return ORTHRUS_EINVAL;
+    c->device = device;
+    c->num_cus = prop.multiProcessorCount;
+    c->err_word = nullptr;
+    if (hipMalloc((void **)&c->err_word, 256) != hipSuccess) { delete c; return ORTHRUS_EHIP; }
+    if (hipMemset(c->err_word, 0, 256) != hipSuccess) { hipFree(c->err_word); delete c; return ORTHRUS_EHIP; }
+    *out = c;
+    return ORTHRUS_OK;
+}
+
+orthrus_status orthrus_destroy(orthrus_ctx *ctx)
+{
+    if (!ctx) return ORTHRUS_EINVAL;
+    hipError_t e = hipFree(ctx->err_word);
+    delete ctx;
+    return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
+int32_t orthrus_attn_num_splits(const orthrus_params *p)
+{
+    orthrus_status s = check_params(p, true, false, true);
+    if (s != ORTHRUS_OK) return (int32_t)s;
+    orthrus::AttnPlan plan;
+    s = make_plan(p, kDefaultCUs, &plan);
+    if (s != ORTHRUS_OK) return (int32_t)s;
+    return plan.num_splits;
+}
+
+int64_t orthrus_attn_workspace_bytes(const orthrus_params *p)
+{
+    orthrus_status s = check_params(p, true, false, true);
+    if (s != ORTHRUS_OK) return (int64_t)s;
+    orthrus::AttnPlan plan;
+    s = make_plan(p, kDefaultCUs, &plan);
+    if (s != ORTHRUS_OK) return (int64_t)s;
+    return (int64_t)(align_up(plan.part_o_bytes, 256) + align_up(plan.part_ml_bytes, 256));
+}
+
+int64_t orthrus_consensus_workspace_bytes(const orthrus_params *p)
+{
+    orthrus_status s = check_params(p, false, true, false);
+    if (s != ORTHRUS_OK) return (int64_t)s;
+    const size_t rows = (size_t)p->batch * p->block_k;
+    const size_t chunks = (size_t)consensus_chunks(p);
+    return (int64_t)(align_up(rows * chunks * sizeof(float), 256) + align_up(rows * chunks * sizeof(int32_t), 256) +
+                     align_up((size_t)p->batch * 2 * sizeof(int32_t), 256));
+}
+
+orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p, orthrus_view view,
+                                      const void *q, const void *k_blk, const void *v_blk,
+                                      const void *k_pool, const void *v_pool,
+                                      const int32_t *page_table, const int32_t *seq_lens,
+                                      void *out, float *lse,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx) return ORTHRUS_EINVAL;
+    orthrus_status s = check_params(p, true, false, true);
+    if (s != ORTHRUS_OK) return s;
+    if (view != ORTHRUS_VIEW_DIFFUSION && view != ORTHRUS_VIEW_AR_VERIFY) return ORTHRUS_EINVAL;
+    if (!q || !k_blk || !v_blk || !k_pool || !v_pool || !page_table || !seq_lens || !out) return ORTHRUS_EINVAL;
+    const uintptr_t al = (uintptr_t)q | (uintptr_t)k_blk | (uintptr_t)v_blk | (uintptr_t)k_pool | (uintptr_t)v_pool |
+                         (uintptr_t)out;
+    if (al & 15) return ORTHRUS_EINVAL;
+    if (p->batch == 0) return ORTHRUS_OK;
+    orthrus::AttnPlan plan;
+    // sized with the same CU count as the workspace query, so both always agree
+    s = make_plan(p, kDefaultCUs, &plan);
+    if (s != ORTHRUS_OK) return s;
+    const size_t need = align_up(plan.part_o_bytes, 256) + align_up(plan.part_ml_bytes, 256);
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return ORTHRUS_EWORKSPACE;
+
+    orthrus::AttnArgs a;
+    a.q = (const uint16_t *)q; a.k_blk = (const uint16_t *)k_blk; a.v_blk = (const uint16_t *)v_blk;
+    a.k_pool = (const uint16_t *)k_pool; a.v_pool = (const uint16_t *)v_pool;
+    a.page_table = page_table; a.seq_lens = seq_lens;
+    a.out = (uint16_t *)out; a.lse = lse;
+    a.part_o = (float *)workspace;
+    a.part_ml = (float *)((char *)workspace + align_up(plan.part_o_bytes, 256));
+    a.err_word = ctx->err_word;
+    a.stride_page = p->pool_stride_page; a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok;
+    a.num_pages = p->num_pages;
+    a.batch = p->batch; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
+    a.group = p->num_q_heads / p->num_kv_heads; a.block_k = p->block_k; a.rows = plan.rows;
+    a.page_shift = log2_exact(p->page_size); a.max_pages_per_seq = p->max_pages_per_seq;
+    a.max_seq_len = p->max_seq_len; a.chunk_tokens = plan.chunk_tokens; a.num_splits = plan.num_splits;
+    a.view = (int)view;
+    a.scale_log2e = p->sm_scale * 1.4426950408889634f;
+    hipError_t e = orthrus::launch_attn(a, plan, p->head_dim, (hipStream_t)stream);
+    return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
+orthrus_status orthrus_consensus_commit(orthrus_ctx *ctx, const orthrus_params *p,
+                                        const float *ar_logits, const int32_t *draft_tokens,
+                                        const void *k_blk_ar, const void *v_blk_ar,
+                                        void *k_pool, void *v_pool,
+                                        const int32_t *page_table, int32_t *seq_lens,
+                                        int32_t *accept_len, int32_t *num_committed,
+                                        int32_t *out_tokens, int32_t *next_anchor,
+                                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx) return ORTHRUS_EINVAL;
+    if ((k_blk_ar == nullptr) != (v_blk_ar == nullptr)) return ORTHRUS_EINVAL;
+    const bool do_commit = k_blk_ar != nullptr;
+    orthrus_status s = check_params(p, false, true, do_commit);
+    if (s != ORTHRUS_OK) return s;
+    if (!ar_logits || !draft_tokens || !accept_len || !num_committed || !out_tokens || !next_anchor)
+        return ORTHRUS_EINVAL;
+    if (((uintptr_t)ar_logits) & 3) return ORTHRUS_EINVAL;
+    if (do_commit) {
+        if (!k_pool || !v_pool || !page_table || !seq_lens || p->num_layers <= 0) return ORTHRUS_EINVAL;
+        if (p->num_layers > 65535) return ORTHRUS_EUNSUPPORTED;
+        const uintptr_t al = (uintptr_t)k_blk_ar | (uintptr_t)v_blk_ar | (uintptr_t)k_pool | (uintptr_t)v_pool;
+        if (al & 15) return ORTHRUS_EINVAL;
+    }
+    if (p->batch == 0) return ORTHRUS_OK;
+    const size_t rows = (size_t)p->batch * p->block_k;
+    const size_t chunks = (size_t)consensus_chunks(p);
+    if (rows * chunks > 0x7fffffffull) return ORTHRUS_EUNSUPPORTED;
+    const size_t o1 = align_up(rows * chunks * sizeof(float), 256);
+    const size_t o2 = o1 + align_up(rows * chunks * sizeof(int32_t), 256);
+    const size_t need = o2 + align_up((size_t)p->batch * 2 * sizeof(int32_t), 256);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return ORTHRUS_EWORKSPACE;
+
+    orthrus::ConsensusArgs a;
+    a.ar_logits = ar_logits; a.draft_tokens = draft_tokens;
+    a.k_blk_ar = (const uint16_t *)k_blk_ar; a.v_blk_ar = (const uint16_t *)v_blk_ar;
+    a.k_pool = (uint16_t *)k_pool; a.v_pool = (uint16_t *)v_pool;
+    a.page_table = page_table; a.seq_lens = seq_lens;
+    a.accept_len = accept_len; a.num_committed = num_committed; a.out_tokens = out_tokens; a.next_anchor = next_anchor;
+    a.part_val = (float *)workspace;
+    a.part_idx = (int32_t *)((char *)workspace + o1);
+    a.commit_info = (int32_t *)((char *)workspace + o2);
+    a.err_word = ctx->err_word;
+    a.stride_layer = p->pool_stride_layer; a.stride_page = p->pool_stride_page;
+    a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok; a.num_pages = p->num_pages;
+    a.batch = p->batch; a.block_k = p->block_k; a.vocab = p->vocab; a.num_layers = p->num_layers;
+    a.num_kv_heads = p->num_kv_heads; a.head_dim = p->head_dim;
+    a.page_shift = do_commit ? log2_exact(p->page_size) : 0; a.max_pages_per_seq = p->max_pages_per_seq;
+    a.chunks = (int)chunks; a.chunk_elems = orthrus::consensus_chunk_elems(); a.do_commit = do_commit ? 1 : 0;
+    hipError_t e = orthrus::launch_consensus(a, (hipStream_t)stream);
+    return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
+orthrus_status orthrus_last_device_error(orthrus_ctx *ctx, void *stream, int32_t *code)
+{
+    if (!ctx || !code) return ORTHRUS_EINVAL;
+    int32_t v = 0;
+    if (hipMemcpyAsync(&v, ctx->err_word, sizeof v, hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess)
+        return ORTHRUS_EHIP;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ORTHRUS_EHIP;
+    if (v != 0) {
+        if (hipMemsetAsync(ctx->err_word, 0, sizeof v, (hipStream_t)stream) != hipSuccess) return ORTHRUS_EHIP;
+        if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ORTHRUS_EHIP;
+    }
+    *code = v;
+    return ORTHRUS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,192 @@
+// Greedy consensus and in-place commit for the Orthrus decode step on gfx950 (Section 3.3,
+// "Architectural Consensus Mechanism", Eq. 8; Fig. 2(b): accepted tokens' KV appended to the
+// shared cache).
+//
+//   argmax_partial_kernel  grid (row * chunks + chunk): each workgroup scans one chunk of one logits row
+//                          with 16-byte loads and reduces (value, index) through wavefront
+//                          shuffles; one (value, index) pair per chunk goes to the workspace.
+//   accept_kernel          grid (sequence): finishes the K row argmaxes, finds the accepted
+//                          prefix with a wavefront ballot, writes tokens/lengths, checks that the
+//                          appended positions are mapped and publishes (old length, rows to append).
+//   commit_kernel          grid (sequence, layer): copies the appended K/V rows into their pages.
+//
+// Order among candidates: a NaN outranks every number, larger values outrank smaller ones, and
+// among equals the smaller index wins; this is a total order, so the result does not depend on
+// how the scan is split.
+#include "orthrus_internal.h"
+
+namespace orthrus {
+
+constexpr int kChunkElems = 8192;  // floats per (row, chunk) workgroup: 32 KiB
+int consensus_chunk_elems() { return kChunkElems; }
+
+// true if candidate (v1, i1) outranks (v2, i2)
+__device__ __forceinline__ bool outranks(float v1, int i1, float v2, int i2)
+{
+    const bool n1 = v1 != v1, n2 = v2 != v2;
+    if (n1 || n2) return (n1 && n2) ? (i1 < i2) : n1;
+    return v1 > v2 || (v1 == v2 && i1 < i2);
+}
+
+// update for a candidate known to sit at a larger index than the current best
+__device__ __forceinline__ void take_later(float v, int i, float &bv, int &bi)
+{
+    if (!(bv != bv) && ((v != v) || v > bv)) { bv = v; bi = i; }
+}
+
+__device__ __forceinline__ void wave_best(float &bv, int &bi)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int oi = __shfl_xor(bi, off);
+        if (outranks(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+}
+
+__global__ void __launch_bounds__(256) argmax_partial_kernel(const ConsensusArgs a)
+{
+    const int row = blockIdx.x / a.chunks, chunk = blockIdx.x - row * a.chunks;
+    const int tid = threadIdx.x;
+    const float *base = a.ar_logits + (int64_t)row * a.vocab;
+    const int begin = chunk * a.chunk_elems;
+    const int end = min(a.vocab, begin + a.chunk_elems);
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    // 16-byte loads need the row start aligned; rows are 4*vocab bytes apart
+    const bool vec_ok = ((a.vocab & 3) == 0) && ((((uintptr_t)a.ar_logits) & 15) == 0);
+    if (vec_ok) {
+        // begin is a multiple of 4 (chunk_elems is); end too since vocab is
+        for (int i = begin + tid * 4; i < end; i += 256 * 4 * 2) {
+            const float4 x = *(const float4 *)(base + i);
+            const int i2 = i + 256 * 4;
+            float4 y = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            const bool has2 = i2 < end;
+            if (has2) y = *(const float4 *)(base + i2);
+            if (bi == 0x7fffffff) { bv = x.x; bi = i; } else take_later(x.x, i, bv, bi);
+            take_later(x.y, i + 1, bv, bi);
+            take_later(x.z, i + 2, bv, bi);
+            take_later(x.w, i + 3, bv, bi);
+            if (has2) {
+                take_later(y.x, i2, bv, bi);
+                take_later(y.y, i2 + 1, bv, bi);
+                take_later(y.z, i2 + 2, bv, bi);
+                take_later(y.w, i2 + 3, bv, bi);
+            }
+        }
+    } else {
+        for (int i = begin + tid; i < end; i += 256) {
+            const float x = base[i];
+            if (bi == 0x7fffffff) { bv = x; bi = i; } else take_later(x, i, bv, bi);
+        }
+    }
+    wave_best(bv, bi);
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w)
+            if (outranks(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+        a.part_val[(int64_t)row * a.chunks + chunk] = bv;
+        a.part_idx[(int64_t)row * a.chunks + chunk] = bi;
+    }
+}
+
+// One wavefront per sequence; lane k < K owns block row k.
+__global__ void __launch_bounds__(64) accept_kernel(const ConsensusArgs a)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int K = a.block_k;
+    int am = -1;
+    bool match = false;
+    if (lane < K) {
+        const int64_t row = (int64_t)b * K + lane;
+        float bv = a.part_val[row * a.chunks];
+        int bi = a.part_idx[row * a.chunks];
+        for (int ch = 1; ch < a.chunks; ++ch) {
+            const float v = a.part_val[row * a.chunks + ch];
+            const int i = a.part_idx[row * a.chunks + ch];
+            if (outranks(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+        am = bi;
+        match = a.draft_tokens[row] == am;
+    }
+    // accepted prefix = run of matching rows starting at row 0
+    const unsigned long long mism = ~__ballot(match);           // lanes >= K never match
+    const int n_acc = mism ? __ffsll((long long)mism) - 1 : 64;  // first mismatching row (<= K)
+    const int m = min(n_acc + 1, K);
+    if (lane < K) a.out_tokens[(int64_t)b * K + lane] = lane < m ? am : -1;
+    const int anchor = __shfl(am, m - 1);
+    int committed = m;
+    if (a.do_commit) {
+        const int L = a.seq_lens[b];
+        bool bad = false;
+        if (lane < m) {
+            const int pos = L + lane;
+            const int slot = pos >> a.page_shift;
+            if (L < 0 || slot >= a.max_pages_per_seq) bad = true;
+            else {
+                const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + slot];
+                bad = pg < 0 || pg >= a.num_pages;
+            }
+        }
+        const bool any_bad = __ballot(bad) != 0ull;
+        if (any_bad) committed = 0;
+        if (lane == 0) {
+            a.commit_info[b * 2] = L;
+            a.commit_info[b * 2 + 1] = committed;
+            if (any_bad) atomicExch(a.err_word, -4);
+            else a.seq_lens[b] = L + m;
+        }
+    }
+    if (lane == 0) {
+        a.accept_len[b] = n_acc;
+        a.num_committed[b] = committed;
+        a.next_anchor[b] = anchor;
+    }
+}
+
+// Append rows 0..m-1 of the AR view's block K/V of (sequence b, layer) at positions L..L+m-1.
+__global__ void __launch_bounds__(256) commit_kernel(const ConsensusArgs a)
+{
+    const int b = blockIdx.x, layer = blockIdx.y;
+    const int L = a.commit_info[b * 2], m = a.commit_info[b * 2 + 1];
+    if (m <= 0) return;
+    const int K = a.block_k, H = a.num_kv_heads, d = a.head_dim;
+    const int cpr = d / 8;                 // 16-byte chunks per row
+    const int per_tok = H * cpr;
+    const int total = m * per_tok;
+    const int P = 1 << a.page_shift;
+    for (int e = threadIdx.x; e < total; e += 256) {
+        const int k = e / per_tok, rem = e - k * per_tok;
+        const int g = rem / cpr, ch = rem - g * cpr;
+        const int pos = L + k;
+        const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + (pos >> a.page_shift)];
+        const int64_t src = ((((int64_t)layer * a.batch + b) * K + k) * H + g) * d + ch * 8;
+        const int64_t dst = (int64_t)layer * a.stride_layer + (int64_t)pg * a.stride_page +
+                            (int64_t)g * a.stride_head + (int64_t)(pos & (P - 1)) * a.stride_tok + ch * 8;
+        *(uint4 *)(a.k_pool + dst) = *(const uint4 *)(a.k_blk_ar + src);
+        *(uint4 *)(a.v_pool + dst) = *(const uint4 *)(a.v_blk_ar + src);
+    }
+}
+
+hipError_t launch_consensus(const ConsensusArgs &a, hipStream_t stream)
+{
+    if (a.batch == 0) return hipSuccess;
+    dim3 g1((unsigned)a.chunks * (unsigned)(a.batch * a.block_k));
+    hipLaunchKernelGGL(argmax_partial_kernel, g1, dim3(256), 0, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(accept_kernel, dim3(a.batch), dim3(64), 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (a.do_commit) {
+        hipLaunchKernelGGL(commit_kernel, dim3(a.batch, a.num_layers), dim3(256), 0, stream, a);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+}  // namespace orthrus

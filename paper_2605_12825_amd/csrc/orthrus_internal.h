@@ -1,0 +1,59 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace orthrus {
+
+// Finite stand-in for "no score seen yet" (keeps exp2(m_old - m_new) free of inf - inf).
+constexpr float kNegBig = -1.0e30f;
+
+struct AttnPlan {
+    int rows;          // R = G * K query rows per KV head
+    int nrb_wave;      // 32-row blocks owned by one wave
+    int wr;            // wave groups along rows (wr * wt == 4 waves per workgroup)
+    int rows_padded;   // wr * nrb_wave * 32
+    int chunk_tokens;  // cache tokens per split (multiple of 128)
+    int num_splits;    // splits per (sequence, KV head)
+    size_t lds_bytes;  // dynamic LDS per workgroup
+    size_t part_o_bytes, part_ml_bytes;  // workspace pieces (0 when num_splits == 1)
+};
+
+struct AttnArgs {
+    const uint16_t *q, *k_blk, *v_blk, *k_pool, *v_pool;
+    const int32_t *page_table, *seq_lens;
+    uint16_t *out;
+    float *lse;
+    float *part_o;   // [unit][split][rows_padded][D] unnormalised partial outputs
+    float *part_ml;  // [unit][split][rows_padded][2] running max (log2 domain) and sum
+    int32_t *err_word;
+    int64_t stride_page, stride_head, stride_tok, num_pages;
+    int batch, num_q_heads, num_kv_heads, group, block_k, rows;
+    int page_shift, max_pages_per_seq, max_seq_len, chunk_tokens, num_splits, view;
+    float scale_log2e;  // sm_scale * log2(e)
+};
+
+struct ConsensusArgs {
+    const float *ar_logits;
+    const int32_t *draft_tokens;
+    const uint16_t *k_blk_ar, *v_blk_ar;
+    uint16_t *k_pool, *v_pool;
+    const int32_t *page_table;
+    int32_t *seq_lens, *accept_len, *num_committed, *out_tokens, *next_anchor;
+    float *part_val;     // [B*K][chunks]
+    int32_t *part_idx;   // [B*K][chunks]
+    int32_t *commit_info;  // [B][2]: length before the step, rows to append (0 = none)
+    int32_t *err_word;
+    int64_t stride_layer, stride_page, stride_head, stride_tok, num_pages;
+    int batch, block_k, vocab, num_layers, num_kv_heads, head_dim;
+    int page_shift, max_pages_per_seq, chunks, chunk_elems, do_commit;
+};
+
+// Host-side launchers (defined next to the kernels).  Return hipSuccess or the launch error.
+hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv_heads, int max_seq_len,
+                     int requested_splits, int num_cus, AttnPlan *plan);
+hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream);
+hipError_t launch_consensus(const ConsensusArgs &a, hipStream_t stream);
+int consensus_chunk_elems();
+
+}  // namespace orthrus

@@ -1,0 +1,102 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its host-side
+argument validation answers without touching a GPU (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_12825_amd as orthrus
+from paper_2605_12825_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "orthrus.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(orthrus_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(orthrus.library_path())
+    names = _declared_functions()
+    assert len(names) >= 9
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTED) == names
+
+
+def test_binding_struct_matches_header_field_order():
+    text = open(os.path.join(ROOT, "include", "orthrus.h")).read()
+    body = text[text.index("typedef struct {"):text.index("} orthrus_params;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b(?:int32_t|int64_t|float)\s+([a-z_]+)\s*;", body)
+    assert fields == [f[0] for f in B.orthrus_params._fields_]
+
+
+def _good():
+    return orthrus.make_params(batch=2, num_q_heads=8, num_kv_heads=2, head_dim=128, block_k=16, page_size=16,
+                               max_pages_per_seq=70, max_seq_len=1000, num_pages=200, vocab=1000)
+
+
+def test_status_strings():
+    for code in (0, -1, -2, -3, -4, -5, 7):
+        assert isinstance(orthrus.orthrus_status_string(code), str) and orthrus.orthrus_status_string(code)
+
+
+def test_workspace_queries_and_split_planning():
+    p = _good()
+    assert orthrus.orthrus_attn_num_splits(p) >= 1
+    assert orthrus.orthrus_attn_workspace_bytes(p) >= 0
+    assert orthrus.orthrus_consensus_workspace_bytes(p) > 0
+    p.num_splits = 1
+    assert orthrus.orthrus_attn_num_splits(p) == 1 and orthrus.orthrus_attn_workspace_bytes(p) == 0
+    p.num_splits = 4
+    n = orthrus.orthrus_attn_num_splits(p)
+    assert 1 <= n <= 4
+    # partials: units * splits * padded rows * (d + 2) floats, padded to 256 bytes
+    assert orthrus.orthrus_attn_workspace_bytes(p) >= 2 * 2 * n * 64 * (128 + 2) * 4
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("batch", -1, B.ORTHRUS_EINVAL),
+    ("num_q_heads", 7, B.ORTHRUS_EINVAL),          # not a multiple of num_kv_heads
+    ("head_dim", 96, B.ORTHRUS_EUNSUPPORTED),
+    ("page_size", 8, B.ORTHRUS_EUNSUPPORTED),
+    ("page_size", 24, B.ORTHRUS_EUNSUPPORTED),
+    ("block_k", 33, B.ORTHRUS_EUNSUPPORTED),
+    ("block_k", 0, B.ORTHRUS_EINVAL),
+    ("max_seq_len", 70 * 16 + 1, B.ORTHRUS_EINVAL),  # longer than the page table can map
+    ("sm_scale", 0.0, B.ORTHRUS_EINVAL),
+    ("pool_stride_tok", 100, B.ORTHRUS_EUNSUPPORTED),
+    ("num_pages", 0, B.ORTHRUS_EINVAL),
+])
+def test_bad_params_are_rejected_on_the_host(field, value, status):
+    p = _good()
+    setattr(p, field, value)
+    with pytest.raises(orthrus.OrthrusError) as e:
+        orthrus.orthrus_attn_workspace_bytes(p)
+    assert e.value.status == status
+
+
+def test_group_times_block_limit():
+    p = orthrus.make_params(batch=1, num_q_heads=64, num_kv_heads=2, head_dim=128, block_k=16, page_size=16,
+                            max_pages_per_seq=8, max_seq_len=100, num_pages=8)
+    with pytest.raises(orthrus.OrthrusError) as e:
+        orthrus.orthrus_attn_num_splits(p)          # 32 * 16 = 512 rows > 256
+    assert e.value.status == B.ORTHRUS_EUNSUPPORTED
+
+
+def test_compute_entry_points_reject_null_context_before_any_launch():
+    p = _good()
+    lib = B._lib
+    st = lib.orthrus_dual_view_attn(None, ctypes.byref(p), 0, None, None, None, None, None, None, None, None, None,
+                                    None, 0, None)
+    assert st == B.ORTHRUS_EINVAL
+    st = lib.orthrus_consensus_commit(None, ctypes.byref(p), None, None, None, None, None, None, None, None, None,
+                                      None, None, None, None, 0, None)
+    assert st == B.ORTHRUS_EINVAL
+    code = ctypes.c_int32(0)
+    assert lib.orthrus_last_device_error(None, None, ctypes.byref(code)) == B.ORTHRUS_EINVAL
+    assert lib.orthrus_destroy(None) == B.ORTHRUS_EINVAL
