@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the Orthrus dual-view decode step's hot path on one MI355X.
+
+One step = diffusion-view block attention + AR-view verification attention over the same paged
+KV cache + greedy consensus + in-place commit of the accepted tokens' K/V (one attention layer,
+synthetic seeded inputs resident in HBM before the timed region).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload long|layer8b|mixed|stress|tiny]
+
+Multi-GPU runs are not part of this build: --gpus above 1 exits with a message.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E published peak
+N_SETS = 4              # rotating sets of block inputs / logits (fresh data every step, cycled)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="long")
+    ap.add_argument("--num-splits", type=int, default=-1, help="-1: the workload's setting; 0: library chooses")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-call-events", action="store_true",
+                    help="do not bracket each library call with events inside the timed region")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, cache, host_sets, cons_sets):
+    """Times the CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import oracle
+    cores = oracle.num_threads()
+    lens = cache["seq_lens"]
+    b = int(np.argmax(lens))                      # one whole sequence, all heads, one view
+    blk = host_sets[0][1]
+    sb = {k: np.ascontiguousarray(v[b:b + 1]) for k, v in blk.items()}
+    pt = np.ascontiguousarray(cache["page_table"][b:b + 1])
+    sl = np.ascontiguousarray(lens[b:b + 1])
+    # keep the sample to roughly 10-30 s of CPU work: shrink the context if the sequence is very long
+    flops = 4.0 * w.num_q_heads * w.block_k * float(sl[0]) * w.head_dim
+    budget = 6e9
+    L_used = int(sl[0])
+    if flops > budget:
+        L_used = max(w.page_size, int(sl[0] * budget / flops) // w.page_size * w.page_size)
+        sl = np.array([L_used], np.int32)
+    t0 = time.perf_counter()
+    oracle.dual_view_attn(oracle.VIEW_AR_VERIFY, w.sm_scale, sb["q"], sb["k_blk"], sb["v_blk"], cache["k_pool"],
+                          cache["v_pool"], pt, sl)
+    t_attn = time.perf_counter() - t0
+    tokens_step = float(lens.astype(np.int64).sum())
+    # attention cost is linear in cached tokens: scale the sample to both views over every sequence
+    est_attn = t_attn * (2.0 * tokens_step / max(L_used, 1))
+    est_cons = 0.0
+    sample = "oracle attention on 1 sequence x %d cached tokens x all %d heads x 1 view" % (L_used, w.num_q_heads)
+    if cons_sets:
+        cs = cons_sets[0]
+        t0 = time.perf_counter()
+        oracle.consensus_commit(np.ascontiguousarray(cs["ar_logits"][:1]), np.ascontiguousarray(cs["draft_tokens"][:1]))
+        est_cons = (time.perf_counter() - t0) * w.batch
+        sample += " + consensus on 1 sequence; scaled linearly to the full step (2 views, %d sequences)" % w.batch
+    else:
+        sample += "; scaled linearly to the full step (2 views, %d sequences)" % w.batch
+    est = est_attn + est_cons
+    return {"value": 1.0 / est, "unit": "steps/s", "cores": cores, "kind": "oracle", "sample": sample,
+            "seconds_measured": round(t_attn, 3)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        log("bench.py: this build measures one MI355X only (no collectives or sharding are part of it); "
+            "--gpus %d is not supported" % args.gpus)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        log("bench.py: no HIP device visible; the hot path has no CPU fallback")
+        sys.exit(3)
+    from orthrus_inputs import WORKLOADS, make_block, make_cache, make_consensus_case
+    from paper_2605_12825_amd import runtime as rt
+
+    total_steps = args.warmup + args.steps
+    w = WORKLOADS[args.workload]
+    w = w.with_(steps=total_steps + 1)           # capacity: the cache grows by <= K tokens per step
+    splits = w.num_splits if args.num_splits < 0 else args.num_splits
+    t_gen = time.perf_counter()
+    cache = make_cache(w)
+    host_sets = []
+    for i in range(N_SETS):
+        base = w.seed * 1000 + 10 * i
+        host_sets.append((make_block(w, base + 1), make_block(w, base + 2)))
+    cons_sets = [make_consensus_case(w, w.seed * 1000 + 10 * i + 3) for i in range(N_SETS)] if w.vocab else []
+    log("generated %s inputs in %.1f s" % (w.name, time.perf_counter() - t_gen))
+
+    dev = torch.device("cuda:0")
+    D = rt.to_device_bits
+    k_pool, v_pool = D(cache["k_pool"]), D(cache["v_pool"])
+    page_table, seq_lens = D(cache["page_table"]), D(cache["seq_lens"])
+    sets = [tuple({k: D(v) for k, v in blk.items()} for blk in pair) for pair in host_sets]
+    csets = [(D(c["ar_logits"]), D(c["draft_tokens"])) for c in cons_sets]
+    B, K = w.batch, w.block_k
+    o_d = torch.empty((B, K, w.num_q_heads, w.head_dim), dtype=torch.int16, device=dev)
+    o_a = torch.empty_like(o_d)
+    acc, ncm, anc = (torch.empty((B,), dtype=torch.int32, device=dev) for _ in range(3))
+    toks = torch.empty((B, K), dtype=torch.int32, device=dev)
+    step = rt.DecodeStep(batch=B, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
+                         block_k=K, page_size=w.page_size, max_pages_per_seq=cache["page_table"].shape[1],
+                         max_seq_len=w.capacity_tokens(), num_pages=cache["num_pages"], vocab=w.vocab,
+                         num_splits=splits)
+    stream = torch.cuda.current_stream()
+    call_events = []
+
+    def run_step(i, record):
+        d, a = sets[i % N_SETS]
+        ev = None
+        if record:
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4 if w.vocab else 3)]
+            ev[0].record(stream)
+        step.attn(0, d["q"], d["k_blk"], d["v_blk"], k_pool, v_pool, page_table, seq_lens, o_d)
+        if record:
+            ev[1].record(stream)
+        step.attn(1, a["q"], a["k_blk"], a["v_blk"], k_pool, v_pool, page_table, seq_lens, o_a)
+        if record:
+            ev[2].record(stream)
+        if w.vocab:
+            lg, dr = csets[i % N_SETS]
+            step.consensus_commit(lg, dr, a["k_blk"], a["v_blk"], k_pool, v_pool, page_table, seq_lens, acc, ncm,
+                                  toks, anc)
+            if record:
+                ev[3].record(stream)
+        if record:
+            call_events.append(ev)
+
+    for i in range(args.warmup):
+        run_step(i, False)
+    torch.cuda.synchronize()
+    lens_before = seq_lens.cpu().numpy().astype(np.int64)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for i in range(args.steps):
+        run_step(args.warmup + i, not args.no_call_events)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    total_ms = e0.elapsed_time(e1)
+    lens_after = seq_lens.cpu().numpy().astype(np.int64)
+    err = step.device_error()
+    if err != 0:
+        log("bench.py: device error word %d after the timed region" % err)
+        sys.exit(4)
+
+    ms_per_step = total_ms / args.steps
+    # algorithmic KV bytes of one attention launch: 2*d*2 bytes per cached token per KV head,
+    # at the mean cached length over the timed steps
+    mean_tokens = 0.5 * (lens_before.sum() + lens_after.sum())
+    kv_bytes = mean_tokens * w.num_kv_heads * 2 * w.head_dim * 2
+    roofline = None
+    extra = {}
+    if call_events:
+        d_ms = np.array([ev[0].elapsed_time(ev[1]) for ev in call_events])
+        a_ms = np.array([ev[1].elapsed_time(ev[2]) for ev in call_events])
+        attn_ms = float(np.concatenate([d_ms, a_ms]).mean())
+        achieved = kv_bytes / (attn_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "kernel": "orthrus_dual_view_attn (attn_split_kernel + attn_combine_kernel)",
+                    "avg_launch_us": round(attn_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(kv_bytes)}
+        extra["diffusion_attn_us"] = round(float(d_ms.mean()) * 1e3, 2)
+        extra["verify_attn_us"] = round(float(a_ms.mean()) * 1e3, 2)
+        if w.vocab:
+            c_ms = np.array([ev[2].elapsed_time(ev[3]) for ev in call_events])
+            extra["consensus_commit_us"] = round(float(c_ms.mean()) * 1e3, 2)
+            extra["consensus_logits_gbs"] = round(B * K * w.vocab * 4 / (float(c_ms.mean()) * 1e-3) / 1e9, 1)
+    extra["kv_read_tbs_whole_step"] = round(2 * kv_bytes / (ms_per_step * 1e-3) / 1e12, 3)
+    extra["tokens_committed_per_step"] = round(float((lens_after - lens_before).sum()) / args.steps / max(B, 1), 3)
+
+    out = {
+        "metric": "draft+verify block-attn steps/s and achieved KV-read HBM TB/s (1 MI355X)",
+        "value": round(1000.0 / ms_per_step, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "description": w.description, "batch": B, "num_q_heads": w.num_q_heads,
+                   "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim, "block_k": K,
+                   "context": int(lens_before.max()), "page_size": w.page_size, "vocab": w.vocab,
+                   "num_splits": step.num_splits, "layers": 1,
+                   "step": "diffusion attn + AR verify attn" + (" + consensus + commit" if w.vocab else "")},
+        "roofline": roofline,
+        "detail": extra,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, cache, host_sets, cons_sets)
+    step.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -316,8 +316,9 @@ def test_multi_layer_commit_and_strided_pool():
     w = Workload(name="ml", batch=3, num_q_heads=8, num_kv_heads=2, head_dim=128, block_k=8,
                  context_range=(0, 90), page_size=16, vocab=3000, accept="uniform", steps=2, seed=21)
     layers = 3
-    caches = [make_cache(w, seed=21 + l) for l in range(layers)]
-    # all layers share one page table / lengths (first layer's)
+    lens = np.array([0, 37, 90], np.int32)
+    caches = [make_cache(w, seed=21 + l, seq_lens=lens) for l in range(layers)]
+    # all layers share one page table / lengths (first layer's); with equal lengths the pools have equal shapes
     kp = np.stack([c["k_pool"] for c in caches]); vp = np.stack([c["v_pool"] for c in caches])
     o, rt = _orthrus()
     cache = dict(caches[0]); cache["k_pool"] = kp; cache["v_pool"] = vp
