@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="long")
     ap.add_argument("--num-splits", type=int, default=-1, help="-1: the workload's setting; 0: library chooses")
+    ap.add_argument("--paging", default="", help="override the workload's page-table layout: contiguous|shuffled|scattered")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-call-events", action="store_true",
                     help="do not bracket each library call with events inside the timed region")
@@ -99,6 +100,8 @@ def main():
     total_steps = args.warmup + args.steps
     w = WORKLOADS[args.workload]
     w = w.with_(steps=total_steps + 1)           # capacity: the cache grows by <= K tokens per step
+    if args.paging:
+        w = w.with_(paging=args.paging)
     splits = w.num_splits if args.num_splits < 0 else args.num_splits
     t_gen = time.perf_counter()
     cache = make_cache(w)
@@ -122,7 +125,8 @@ def main():
     toks = torch.empty((B, K), dtype=torch.int32, device=dev)
     step = rt.DecodeStep(batch=B, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
                          block_k=K, page_size=w.page_size, max_pages_per_seq=cache["page_table"].shape[1],
-                         max_seq_len=w.capacity_tokens(), num_pages=cache["num_pages"], vocab=w.vocab,
+                         max_seq_len=min(w.capacity_tokens(), cache["page_table"].shape[1] * w.page_size),
+                         num_pages=cache["num_pages"], vocab=w.vocab,
                          num_splits=splits)
     stream = torch.cuda.current_stream()
     call_events = []

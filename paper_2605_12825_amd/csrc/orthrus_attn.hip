@@ -28,6 +28,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(4))) int32_t const_i32;
 
 union Frag {
     uint4 u;
@@ -93,7 +94,7 @@ __global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs a)
     const int K = a.block_k, G = a.group;
     const int P = 1 << a.page_shift;
 
-    int L = a.seq_lens[b];
+    int L = ((const const_i32 *)a.seq_lens)[b];
     if (L < 0 || L > a.max_seq_len) {
         if (tid == 0) atomicExch(a.err_word, -4);
         L = L < 0 ? 0 : a.max_seq_len;
@@ -103,25 +104,8 @@ __global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs a)
     const int t_end = min(L, t_begin + a.chunk_tokens);
     const int n_tiles = t_end > t_begin ? (t_end - t_begin + 31) >> 5 : 0;
 
-    // ---- queries: B operand of S^T = K.Q^T, lane holds row `col`, d = 16*kk + 8*h .. +7
-    Frag qf[NRB][KSTEPS];
+    Frag qf[NRB][KSTEPS];  // filled after the first tile's loads are on their way
     int irow[NRB];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        const int ridx = (wr * NRB + rb) * 32 + col;
-        if (ridx < a.rows) {
-            const int i = ridx / G, hl = ridx - i * G;
-            irow[rb] = i;
-            const uint16_t *qp = a.q + (((int64_t)b * K + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
-#pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) qf[rb][kk].u = *(const uint4 *)(qp + kk * 16 + h * 8);
-        } else {
-            irow[rb] = 31;  // padding rows see every in-block key; their output is never stored
-#pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) qf[rb][kk].u = make_uint4(0, 0, 0, 0);
-        }
-    }
-
     f32x16 o[NRB][DBLK];
     float m_run[NRB], l_run[NRB];
 #pragma unroll
@@ -138,17 +122,22 @@ __global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs a)
     unsigned char *stage_base = smem + wave * (4 * TILE_B);
     const uint32_t stage_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)stage_base;
     const int ld_tok = lane / CH, ld_ch = lane % CH;  // this lane's (row, slot) inside one wave-wide load
-    const int32_t *pt_row = a.page_table + (int64_t)b * a.max_pages_per_seq;
+    // The page table and lengths are read-only for the whole launch and every index used here is
+    // wave-uniform: reading them through the constant address space makes these scalar loads
+    // (s_load_dword), which keeps them off the vector-memory counter that paces the tile loads.
+    const const_i32 *pt_row = (const const_i32 *)(a.page_table + (int64_t)b * a.max_pages_per_seq);
     const float c = a.scale_log2e;
 
     // Direct global->LDS load of 64 x 16 bytes: lane's bytes land at lds_addr + lane*16.  Issued
     // through inline assembly so that the wave can keep a whole tile in flight while it computes on
     // the other stage; completion is awaited explicitly with s_waitcnt vmcnt (loads return in order).
+    // M0 carries the LDS destination; nothing else in this kernel reads M0, and the compiler
+    // rewrites M0 itself right before any instruction of its own that needs it.
     auto dma16 = [&](const uint16_t *gp, uint32_t lds_addr) __attribute__((always_inline)) {
         asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                      :
                      : "v"(gp), "s"(lds_addr)
-                     : "memory", "m0");
+                     : "memory");
     };
     // page ids of the two 16-token halves of cache tile j (second = first when the half is past t_end)
     auto tile_pages = [&](int j, int &pg0, int &pg1) __attribute__((always_inline)) {
@@ -292,6 +281,29 @@ __global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs a)
     } else if (do_block) {
         issue_block(0);
     }
+
+    // ---- queries: B operand of S^T = K.Q^T, lane holds row `col`, d = 16*kk + 8*h .. +7
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int ridx = (wr * NRB + rb) * 32 + col;
+        if (ridx < a.rows) {
+            const int i = ridx / G, hl = ridx - i * G;
+            irow[rb] = i;
+            const uint16_t *qp = a.q + (((int64_t)b * K + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) qf[rb][kk].u = *(const uint4 *)(qp + kk * 16 + h * 8);
+        } else {
+            irow[rb] = 31;  // padding rows see every in-block key; their output is never stored
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) qf[rb][kk].u = make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    // Every vector load the compiler knows about (the queries) is waited for here, before the loop:
+    // inside the loop only the hand-issued tile loads are outstanding, so the compiler adds no
+    // vmcnt wait of its own there (such a wait would also drain the tile that is being prefetched).
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0), other counters untouched
+
     for (int i = 0; i < total; ++i) {
         const int st = i & 1;
         const int nx = i + 1;
