@@ -10,10 +10,9 @@ constexpr float kNegBig = -1.0e30f;
 
 struct AttnPlan {
     int rows;          // R = G * K query rows per KV head
-    int nrb_wave;      // 32-row blocks owned by one wave
-    int wr;            // wave groups along rows (wr * wt == 4 waves per workgroup)
-    int rows_padded;   // wr * nrb_wave * 32
-    int chunk_tokens;  // cache tokens per split (multiple of 128)
+    int waves;         // waves per workgroup = 32-row blocks (1, 2, 4 or 8)
+    int rows_padded;   // waves * 32
+    int chunk_tokens;  // cache tokens per split (multiple of 32)
     int num_splits;    // splits per (sequence, KV head)
     size_t lds_bytes;  // dynamic LDS per workgroup
     size_t part_o_bytes, part_ml_bytes;  // workspace pieces (0 when num_splits == 1)
@@ -24,8 +23,8 @@ struct AttnArgs {
     const int32_t *page_table, *seq_lens;
     uint16_t *out;
     float *lse;
-    float *part_o;   // [unit][split][rows_padded][D] unnormalised partial outputs
-    float *part_ml;  // [unit][split][rows_padded][2] running max (log2 domain) and sum
+    float *part_o;   // [unit][split][wave][d block][4][lane] float4: unnormalised partial outputs, register order
+    float *part_ml;  // [unit][split][wave][32 rows] float2: running max (log2 domain) and sum
     int32_t *err_word;
     int64_t stride_page, stride_head, stride_tok, num_pages;
     int batch, num_q_heads, num_kv_heads, group, block_k, rows;
