@@ -33,12 +33,15 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 typedef __attribute__((address_space(4))) int32_t const_i32;
 
 union Frag {
     uint4 u;
     bf16x8 v;
     s16x4 h[2];
+    u32x4 n;
 };
 
 // LDS tile layout.  A wave-wide 16-byte direct load fills 1024 contiguous LDS bytes = one "group" of
@@ -49,6 +52,7 @@ union Frag {
 // consecutive rows, same chunk) and the V transpose read (16 lanes = 4 rows x 32 bytes).  The
 // permutation is applied on the global side (a lane fetches the chunk that belongs in its slot).
 constexpr int kGroupStride = 1040;
+constexpr float kLazy = 8.0f;  // log2 of the largest exponential the lazy softmax reference allows
 template <int CH>
 __device__ __forceinline__ int xm(int r)
 {
@@ -59,6 +63,19 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
     f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));  // v_cvt_pk_bf16_f32, RNE
+}
+
+// Combine a value with the one held by lane ^ 32 (the other half-wave) without going through LDS:
+// v_permlane32_swap exchanges the upper half of one register with the lower half of another.
+__device__ __forceinline__ float max_with_other_half(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_with_other_half(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 // Plain workgroup barrier.  Tile loads are tracked by hand (vmcnt), LDS traffic of the compiler's own
@@ -239,6 +256,7 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
     // ---- main loop: one barrier per tile.  Before it, this wave's loads of tile i are complete; after
     //      it, so are everybody's, and everybody is done reading stage (i-1) % NS, which is refilled
     //      with tile i+NS-1 while tile i is computed.
+    int stage = 0;  // ring slot of tile i (= i % NS)
     for (int i = 0; i < n_tiles; ++i) {
         const int ahead = min(NS - 2, n_tiles - 1 - i);  // tiles issued after tile i so far
         if (ahead >= 2) wait_vmcnt<2 * MY>();
@@ -247,7 +265,14 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
         wg_barrier();
         if (i + NS - 1 < n_tiles) issue_tile(i + NS - 1);
 
-        const unsigned char *tile = smem + (i % NS) * STAGE_B;
+        // LDS addresses of this tile's operands: one add per base, the rest are instruction offsets
+        const uint32_t st_addr = smem_lds + (uint32_t)stage * STAGE_B;
+        stage = stage + 1 == NS ? 0 : stage + 1;
+        uint32_t ka[KSTEPS / 2], va_[DBLK];
+#pragma unroll
+        for (int q = 0; q < KSTEPS / 2; ++q) ka[q] = st_addr + kb[q];
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) va_[db] = st_addr + vb[db];
         // lim = number of leading tile tokens this lane's row may see
         int lim = 32;
         if (i < n_cache) lim = t_end - (t_begin + i * 32);
@@ -256,12 +281,22 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        Frag kf[KSTEPS];  // all K operand reads are issued before the first product needs one
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            Frag ka;
-            ka.u = *(const uint4 *)(tile + kb[kk >> 1] + ((kk & 1) << 5));
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, qf[kk].v, s, 0, 0, 0);
-        }
+        for (int kk = 0; kk < KSTEPS; ++kk) kf[kk].n = *(const lds_u32x4 *)(uintptr_t)(ka[kk >> 1] + ((kk & 1) << 5));
+        __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products (the scheduler would pair them up)
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk].v, qf[kk].v, s, 0, 0, 0);
+        // first half of the V operand reads goes out now, so that their latency hides behind the softmax
+        constexpr int VPRE = DBLK / 2;
+        Frag vf[DBLK][2];
+#pragma unroll
+        for (int db = 0; db < VPRE; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                vf[db][q4 >> 1].h[q4 & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (lds_s16x4 *)(uintptr_t)(va_[db] + q4 * (8 / RPI) * GS));
+        __builtin_amdgcn_sched_barrier(0);
         if (lim < 32) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -272,42 +307,50 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
         float mx = s[0];
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * c);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        mx = max_with_other_half(mx);
+        // Online softmax with a lazily updated reference maximum (log2 domain): the reference only
+        // moves when the running maximum has grown by more than kLazy, so exponentials stay below
+        // 2^kLazy and the rescale of the accumulator is skipped for almost every tile.  The result
+        // is unchanged: numerator and denominator always share the same reference.
+        const float m_cand = fmaxf(m_run, mx * c);
+        if (__any(m_cand - m_run > kLazy)) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_cand);
+            m_run = m_cand;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        }
         float p[16];
         float sum = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            p[r] = __builtin_amdgcn_exp2f(s[r] * c - m_new);
+            p[r] = __builtin_amdgcn_exp2f(s[r] * c - m_run);
             sum += p[r];
         }
-        l_run = l_run * alpha + sum;
+        l_run += sum;
         Frag p1, p2;
         p1.u = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
         p2.u = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]),
                           pack_bf16(p[14], p[15]));
-#pragma unroll
-        for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
         // O^T += V^T P^T.  MFMA k-slot (h, j) of the first product is token 8*(j/4) + 4*h + j%4 (what
         // registers 0..7 of S^T hold); the second product is 16 tokens further.
 #pragma unroll
-        for (int db = 0; db < DBLK; ++db) {
-            Frag va[2];
+        for (int db = VPRE; db < DBLK; ++db)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4)
-                va[q4 >> 1].h[q4 & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (lds_s16x4 *)(tile + vb[db] + q4 * (8 / RPI) * GS));
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[0].v, p1.v, o[db], 0, 0, 0);
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1].v, p2.v, o[db], 0, 0, 0);
+                vf[db][q4 >> 1].h[q4 & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (lds_s16x4 *)(uintptr_t)(va_[db] + q4 * (8 / RPI) * GS));
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) {
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][0].v, p1.v, o[db], 0, 0, 0);
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][1].v, p2.v, o[db], 0, 0, 0);
         }
     }
 
     // ---- write-out: this wave's 32 rows
-    l_run += __shfl_xor(l_run, 32);
+    l_run = sum_with_other_half(l_run);
     if (a.num_splits == 1) {
         if (ridx < a.rows) {
             const int i = irow, hl = ridx - i * G;
