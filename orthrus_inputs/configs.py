@@ -68,7 +68,7 @@ WORKLOADS = {
         description="batch 16, 28/4 heads, d=128, context U[512,8192], K=32, pages scattered in a shared pool"),
     "long": Workload(
         name="long", batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, block_k=16,
-        context=32768, paging="shuffled", vocab=128256, accept="geometric", num_splits=64, seed=1003,
+        context=32768, paging="shuffled", vocab=128256, accept="geometric", seed=1003,
         description="batch 4, 32/8 heads, d=128, context 32768, K=16, 16-token pages, vocab 128256"),
     "stress": Workload(
         name="stress", batch=64, num_q_heads=32, num_kv_heads=8, head_dim=128, block_k=16,
