@@ -12,6 +12,7 @@
  *     hipStream_t passed as void*; NULL = the default stream), do not synchronise with the
  *     host and do not allocate.  Sequence lengths live on the device and are read by the
  *     kernels, so consecutive decode steps can be queued without a host round trip.
+ *   - The context holds one device error word shared by every call made with it.
  *   - Every function returns an orthrus_status.  Argument errors are found on the host before
  *     anything is launched; on such an error nothing has been written.
  *   - Layouts are row-major with the last index contiguous.  bf16 means the upper 16 bits of
@@ -119,7 +120,8 @@ int32_t orthrus_attn_num_splits(const orthrus_params *p);
  * for the value product, bf16 output.
  * Device-side errors: a page id outside [0, num_pages) for a token below seq_lens[b], or
  * seq_lens[b] outside [0, max_seq_len], sets the context's error word (ORTHRUS_ECAPACITY);
- * the affected tokens are treated as absent, nothing is read out of bounds.
+ * tokens behind a bad page id are read from page 0 instead (that sequence's output is then
+ * meaningless), nothing is read out of bounds.
  */
 orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p, orthrus_view view,
                                       const void *q, const void *k_blk, const void *v_blk,

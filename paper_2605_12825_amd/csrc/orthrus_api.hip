@@ -14,6 +14,10 @@ struct orthrus_ctx {
 };
 
 namespace {
+constexpr size_t kCtxWords = 64;
+}
+
+namespace {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -105,8 +109,8 @@ orthrus_status orthrus_create(orthrus_ctx **out, int device)
     c->device = device;
     c->num_cus = prop.multiProcessorCount;
     c->err_word = nullptr;
-    if (hipMalloc((void **)&c->err_word, 256) != hipSuccess) { delete c; return ORTHRUS_EHIP; }
-    if (hipMemset(c->err_word, 0, 256) != hipSuccess) { hipFree(c->err_word); delete c; return ORTHRUS_EHIP; }
+    if (hipMalloc((void **)&c->err_word, kCtxWords * sizeof(int32_t)) != hipSuccess) { delete c; return ORTHRUS_EHIP; }
+    if (hipMemset(c->err_word, 0, kCtxWords * sizeof(int32_t)) != hipSuccess) { hipFree(c->err_word); delete c; return ORTHRUS_EHIP; }
     *out = c;
     return ORTHRUS_OK;
 }

@@ -481,13 +481,34 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     if (requested_splits > 0) {
         splits = requested_splits;
     } else {
-        // fill every resident slot once, but keep at least 512 cached tokens per split so that the
-        // fp32 partial (rows x d x 4 bytes per split) stays a few percent of the KV bytes streamed
+        // Pick the split count with a small cost model (times in microseconds), using max_seq_len for
+        // every sequence: workgroups run in rounds of `slots`; a round streams at the practical HBM
+        // rate once every CU holds at least 4 streaming waves; every split beyond the first writes and
+        // re-reads an fp32 partial (rows x d x 4 bytes) and adds the combine launch.
+        const double kRate = 6.0e6;          // bytes per microsecond (practical streaming ceiling)
+        const double kRound = 5.0, kCombine = 8.0;
         const int64_t slots = (int64_t)num_cus * per_cu;
-        const int64_t want = (slots + units - 1) / (units > 0 ? units : 1);
-        const int64_t by_len = (max_seq_len + 511) / 512;
-        splits = (int)(want < by_len ? want : by_len);
-        if (splits < 1) splits = 1;
+        const double row_bytes = 2.0 * head_dim * 2.0;  // K + V bytes per cached token per KV head
+        const double part_bytes = 2.0 * plan->rows_padded * head_dim * 4.0;  // written once, read once
+        const int max_s = max_seq_len >= 256 ? (max_seq_len / 128 < 64 ? max_seq_len / 128 : 64) : 1;
+        double best = 1e300;
+        splits = 1;
+        for (int s = 1; s <= max_s; ++s) {
+            const int64_t wgs = units * s;
+            const double per_wg = row_bytes * ((double)max_seq_len / s) + (s > 1 ? part_bytes : 0.0);
+            double t = s > 1 ? kCombine : 0.0;
+            for (int64_t left = wgs; left > 0; left -= slots) {
+                const int64_t now = left < slots ? left : slots;
+                // workgroups spread over the CUs first; a CU streams at its share of the HBM rate once
+                // it holds at least 4 waves
+                const double active = now < num_cus ? (double)now : (double)num_cus;
+                double per_cu_waves = (double)now * W / active / 4.0;
+                if (per_cu_waves > 1.0) per_cu_waves = 1.0;
+                const double f = active / num_cus * per_cu_waves;
+                t += kRound + per_wg * now / (kRate * f);
+            }
+            if (t < best * 0.98) { best = t; splits = s; }  // prefer fewer splits unless clearly better
+        }
     }
     int chunk = (max_seq_len + splits - 1) / splits;
     chunk = ((chunk + 31) / 32) * 32;

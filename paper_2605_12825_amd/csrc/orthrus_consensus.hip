@@ -2,13 +2,18 @@
 // "Architectural Consensus Mechanism", Eq. 8; Fig. 2(b): accepted tokens' KV appended to the
 // shared cache).
 //
-//   argmax_partial_kernel  grid (row * chunks + chunk): each workgroup scans one chunk of one logits row
-//                          with 16-byte loads and reduces (value, index) through wavefront
+//   argmax_partial_kernel  grid (row * chunks + chunk): each workgroup scans one chunk of one logits
+//                          row with 16-byte loads and reduces (value, index) through wavefront
 //                          shuffles; one (value, index) pair per chunk goes to the workspace.
-//   accept_kernel          grid (sequence): finishes the K row argmaxes, finds the accepted
-//                          prefix with a wavefront ballot, writes tokens/lengths, checks that the
-//                          appended positions are mapped and publishes (old length, rows to append).
-//   commit_kernel          grid (sequence, layer): copies the appended K/V rows into their pages.
+//   accept_commit_kernel   grid (sequence): the first wave finishes the K row argmaxes, finds the
+//                          accepted prefix with a wavefront ballot, writes tokens/lengths and checks
+//                          that the appended positions are mapped; then the whole workgroup copies
+//                          the appended K/V rows into their pages (up to kInlineLayers layers).
+//   commit_kernel          grid (sequence, layer): the same copy as its own launch when there are
+//                          more layers than one workgroup should copy.
+// (A single-launch variant in which the last-arriving workgroup of a sequence finishes the job was
+// measured and dropped: the device-scope release/acquire fences it needs per workgroup cost far
+// more than the two extra launches.)
 //
 // Order among candidates: a NaN outranks every number, larger values outrank smaller ones, and
 // among equals the smaller index wins; this is a total order, so the result does not depend on
@@ -41,6 +46,29 @@ __device__ __forceinline__ void wave_best(float &bv, int &bi)
         const float ov = __shfl_xor(bv, off);
         const int oi = __shfl_xor(bi, off);
         if (outranks(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+}
+
+constexpr int kInlineLayers = 2;
+
+// Copy rows 0..m-1 of the AR view's block K/V of (sequence b, layer) to token positions L..L+m-1.
+__device__ __forceinline__ void append_rows(const ConsensusArgs &a, int b, int layer, int L, int m, int tid, int nthreads)
+{
+    const int K = a.block_k, H = a.num_kv_heads, d = a.head_dim;
+    const int cpr = d / 8;  // 16-byte chunks per row
+    const int per_tok = H * cpr;
+    const int total = m * per_tok;
+    const int P = 1 << a.page_shift;
+    for (int e = tid; e < total; e += nthreads) {
+        const int k = e / per_tok, rem = e - k * per_tok;
+        const int g = rem / cpr, ch = rem - g * cpr;
+        const int pos = L + k;
+        const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + (pos >> a.page_shift)];
+        const int64_t src = ((((int64_t)layer * a.batch + b) * K + k) * H + g) * d + ch * 8;
+        const int64_t dst = (int64_t)layer * a.stride_layer + (int64_t)pg * a.stride_page +
+                            (int64_t)g * a.stride_head + (int64_t)(pos & (P - 1)) * a.stride_tok + ch * 8;
+        *(uint4 *)(a.k_pool + dst) = *(const uint4 *)(a.k_blk_ar + src);
+        *(uint4 *)(a.v_pool + dst) = *(const uint4 *)(a.v_blk_ar + src);
     }
 }
 
@@ -94,82 +122,77 @@ __global__ void __launch_bounds__(256) argmax_partial_kernel(const ConsensusArgs
     }
 }
 
-// One wavefront per sequence; lane k < K owns block row k.
-__global__ void __launch_bounds__(64) accept_kernel(const ConsensusArgs a)
+__global__ void __launch_bounds__(256) accept_commit_kernel(const ConsensusArgs a)
 {
-    const int b = blockIdx.x, lane = threadIdx.x;
+    const int b = blockIdx.x, tid = threadIdx.x;
     const int K = a.block_k;
-    int am = -1;
-    bool match = false;
-    if (lane < K) {
-        const int64_t row = (int64_t)b * K + lane;
-        float bv = a.part_val[row * a.chunks];
-        int bi = a.part_idx[row * a.chunks];
-        for (int ch = 1; ch < a.chunks; ++ch) {
-            const float v = a.part_val[row * a.chunks + ch];
-            const int i = a.part_idx[row * a.chunks + ch];
-            if (outranks(v, i, bv, bi)) { bv = v; bi = i; }
+    __shared__ int s_L, s_m;
+    // ---- accept: the first wave, lane k < K owns block row k of sequence b
+    if (tid < 64) {
+        const int lane = tid;
+        int am = -1;
+        bool match = false;
+        if (lane < K) {
+            const int64_t r = (int64_t)b * K + lane;
+            float v0 = a.part_val[r * a.chunks];
+            int i0 = a.part_idx[r * a.chunks];
+            for (int ch = 1; ch < a.chunks; ++ch) {
+                const float v = a.part_val[r * a.chunks + ch];
+                const int i = a.part_idx[r * a.chunks + ch];
+                if (outranks(v, i, v0, i0)) { v0 = v; i0 = i; }
+            }
+            am = i0;
+            match = a.draft_tokens[r] == am;
         }
-        am = bi;
-        match = a.draft_tokens[row] == am;
-    }
-    // accepted prefix = run of matching rows starting at row 0
-    const unsigned long long mism = ~__ballot(match);           // lanes >= K never match
-    const int n_acc = mism ? __ffsll((long long)mism) - 1 : 64;  // first mismatching row (<= K)
-    const int m = min(n_acc + 1, K);
-    if (lane < K) a.out_tokens[(int64_t)b * K + lane] = lane < m ? am : -1;
-    const int anchor = __shfl(am, m - 1);
-    int committed = m;
-    if (a.do_commit) {
-        const int L = a.seq_lens[b];
-        bool bad = false;
-        if (lane < m) {
-            const int pos = L + lane;
-            const int slot = pos >> a.page_shift;
-            if (L < 0 || slot >= a.max_pages_per_seq) bad = true;
-            else {
-                const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + slot];
-                bad = pg < 0 || pg >= a.num_pages;
+        // accepted prefix = run of matching rows starting at row 0
+        const unsigned long long mism = ~__ballot(match);           // lanes >= K never match
+        const int n_acc = mism ? __ffsll((long long)mism) - 1 : 64;  // first mismatching row (<= K)
+        const int m = min(n_acc + 1, K);
+        if (lane < K) a.out_tokens[(int64_t)b * K + lane] = lane < m ? am : -1;
+        const int anchor = __shfl(am, m - 1);
+        int committed = m;
+        int L = 0;
+        if (a.do_commit) {
+            L = a.seq_lens[b];
+            bool bad = false;
+            if (lane < m) {
+                const int pos = L + lane;
+                const int slot = pos >> a.page_shift;
+                if (L < 0 || slot >= a.max_pages_per_seq) bad = true;
+                else {
+                    const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + slot];
+                    bad = pg < 0 || pg >= a.num_pages;
+                }
+            }
+            const bool any_bad = __ballot(bad) != 0ull;
+            if (any_bad) committed = 0;
+            if (lane == 0) {
+                a.commit_info[b * 2] = L;
+                a.commit_info[b * 2 + 1] = committed;
+                if (any_bad) atomicExch(a.err_word, -4);
+                else a.seq_lens[b] = L + m;
             }
         }
-        const bool any_bad = __ballot(bad) != 0ull;
-        if (any_bad) committed = 0;
         if (lane == 0) {
-            a.commit_info[b * 2] = L;
-            a.commit_info[b * 2 + 1] = committed;
-            if (any_bad) atomicExch(a.err_word, -4);
-            else a.seq_lens[b] = L + m;
+            a.accept_len[b] = n_acc;
+            a.num_committed[b] = committed;
+            a.next_anchor[b] = anchor;
+            s_L = L;
+            s_m = a.do_commit ? committed : 0;
         }
     }
-    if (lane == 0) {
-        a.accept_len[b] = n_acc;
-        a.num_committed[b] = committed;
-        a.next_anchor[b] = anchor;
-    }
+    __syncthreads();
+    // ---- commit: the whole workgroup copies the appended rows when there are few layers
+    if (a.do_commit && a.num_layers <= kInlineLayers && s_m > 0)
+        for (int layer = 0; layer < a.num_layers; ++layer) append_rows(a, b, layer, s_L, s_m, tid, 256);
 }
 
-// Append rows 0..m-1 of the AR view's block K/V of (sequence b, layer) at positions L..L+m-1.
+// The same copy as its own launch: grid (sequence, layer).
 __global__ void __launch_bounds__(256) commit_kernel(const ConsensusArgs a)
 {
     const int b = blockIdx.x, layer = blockIdx.y;
     const int L = a.commit_info[b * 2], m = a.commit_info[b * 2 + 1];
-    if (m <= 0) return;
-    const int K = a.block_k, H = a.num_kv_heads, d = a.head_dim;
-    const int cpr = d / 8;                 // 16-byte chunks per row
-    const int per_tok = H * cpr;
-    const int total = m * per_tok;
-    const int P = 1 << a.page_shift;
-    for (int e = threadIdx.x; e < total; e += 256) {
-        const int k = e / per_tok, rem = e - k * per_tok;
-        const int g = rem / cpr, ch = rem - g * cpr;
-        const int pos = L + k;
-        const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + (pos >> a.page_shift)];
-        const int64_t src = ((((int64_t)layer * a.batch + b) * K + k) * H + g) * d + ch * 8;
-        const int64_t dst = (int64_t)layer * a.stride_layer + (int64_t)pg * a.stride_page +
-                            (int64_t)g * a.stride_head + (int64_t)(pos & (P - 1)) * a.stride_tok + ch * 8;
-        *(uint4 *)(a.k_pool + dst) = *(const uint4 *)(a.k_blk_ar + src);
-        *(uint4 *)(a.v_pool + dst) = *(const uint4 *)(a.v_blk_ar + src);
-    }
+    if (m > 0) append_rows(a, b, layer, L, m, threadIdx.x, 256);
 }
 
 hipError_t launch_consensus(const ConsensusArgs &a, hipStream_t stream)
@@ -179,10 +202,10 @@ hipError_t launch_consensus(const ConsensusArgs &a, hipStream_t stream)
     hipLaunchKernelGGL(argmax_partial_kernel, g1, dim3(256), 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(accept_kernel, dim3(a.batch), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL(accept_commit_kernel, dim3(a.batch), dim3(256), 0, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (a.do_commit) {
+    if (a.do_commit && a.num_layers > kInlineLayers) {
         hipLaunchKernelGGL(commit_kernel, dim3(a.batch, a.num_layers), dim3(256), 0, stream, a);
         e = hipGetLastError();
     }
