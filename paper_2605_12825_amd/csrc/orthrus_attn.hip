@@ -163,13 +163,23 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
     // Start this wave's share of the loads of tile t (cache tile, or the in-block tile when
     // t == n_cache) into ring stage t % NS.  Rows past the end repeat the last valid row (finite data,
     // masked later): nothing is fetched through an unmapped page and no LDS row is left undefined.
-    auto issue_tile = [&](int t) __attribute__((always_inline)) {
+    // Page ids of the two 16-token halves of cache tile t (the second repeats the first when that
+    // half lies past the end).  They are fetched one tile ahead of their use, so that the scalar
+    // load's latency is never in front of a tile's loads.
+    auto fetch_pages = [&](int t, int &p0, int &p1) __attribute__((always_inline)) {
+        p0 = 0;
+        p1 = 0;
+        if (t < n_cache) {
+            const int ts = t_begin + t * 32;
+            p0 = pt_row[ts >> a.page_shift];
+            p1 = p0;
+            if (ts + 16 < t_end) p1 = pt_row[(ts + 16) >> a.page_shift];
+        }
+    };
+    auto issue_tile = [&](int t, int p0, int p1) __attribute__((always_inline)) {
         const uint32_t dst = smem_lds + (t % NS) * STAGE_B;
         if (t < n_cache) {
             const int ts = t_begin + t * 32;
-            int p0 = pt_row[ts >> a.page_shift];
-            int p1 = p0;
-            if (ts + 16 < t_end) p1 = pt_row[(ts + 16) >> a.page_shift];
             if (p0 < 0 || p0 >= a.num_pages || p1 < 0 || p1 >= a.num_pages) {
                 if (lane == 0) atomicExch(a.err_word, -4);
                 if (p0 < 0 || p0 >= a.num_pages) p0 = 0;
@@ -202,9 +212,13 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
     };
 
     // ---- prologue: fill the ring, then fetch the queries while those loads are in flight
+    int np0, np1;  // page ids of the next tile to be issued
 #pragma unroll
-    for (int t = 0; t < NS - 1; ++t)
-        if (t < n_tiles) issue_tile(t);
+    for (int t = 0; t < NS - 1; ++t) {
+        fetch_pages(t, np0, np1);
+        if (t < n_tiles) issue_tile(t, np0, np1);
+    }
+    fetch_pages(NS - 1, np0, np1);
 
     // queries: B operand of S^T = K.Q^T, lane holds row `col` of this wave's block, d = 16*kk + 8*h .. +7
     Frag qf[KSTEPS];
@@ -263,7 +277,8 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
         else if (ahead == 1) wait_vmcnt<MY>();
         else wait_vmcnt<0>();
         wg_barrier();
-        if (i + NS - 1 < n_tiles) issue_tile(i + NS - 1);
+        if (i + NS - 1 < n_tiles) issue_tile(i + NS - 1, np0, np1);
+        fetch_pages(i + NS, np0, np1);
 
         // LDS addresses of this tile's operands: one add per base, the rest are instruction offsets
         const uint32_t st_addr = smem_lds + (uint32_t)stage * STAGE_B;
