@@ -28,7 +28,8 @@ N_SETS = 4              # rotating sets of block inputs / logits (fresh data eve
 # HBM bytes per orthrus_dual_view_attn call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (counters scaled by what they read for a plain 1 GiB copy; see profiles/), keyed by
 # (workload, splits).  Reads + writes of the split kernel and the combine kernel.
-MEASURED_TRAFFIC_BYTES = {("long", 24): int((542.23 + 26.79 + 25.56 + 0.52) * 1e6)}
+MEASURED_TRAFFIC_BYTES = {("long", 16): int((542.22 + 17.87 + 17.04 + 0.52) * 1e6),
+                          ("stress", 1): int((558.66 + 8.39) * 1e6)}
 
 
 def log(*a):
