@@ -107,7 +107,8 @@ def main():
 
     total_steps = args.warmup + args.steps
     w = WORKLOADS[args.workload]
-    w = w.with_(steps=total_steps + 1)           # capacity: the cache grows by <= K tokens per step
+    # capacity: the cache grows by <= K tokens per committed step (never, for a workload without consensus)
+    w = w.with_(steps=(total_steps + 1) if w.vocab else 0)
     if args.paging:
         w = w.with_(paging=args.paging)
     splits = w.num_splits if args.num_splits < 0 else args.num_splits
@@ -131,15 +132,19 @@ def main():
     o_a = torch.empty_like(o_d)
     acc, ncm, anc = (torch.empty((B,), dtype=torch.int32, device=dev) for _ in range(3))
     toks = torch.empty((B, K), dtype=torch.int32, device=dev)
+    len0 = int(cache["seq_lens"].max())
+    cap = min(w.capacity_tokens(), cache["page_table"].shape[1] * w.page_size)
     step = rt.DecodeStep(batch=B, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
                          block_k=K, page_size=w.page_size, max_pages_per_seq=cache["page_table"].shape[1],
-                         max_seq_len=min(w.capacity_tokens(), cache["page_table"].shape[1] * w.page_size),
-                         num_pages=cache["num_pages"], vocab=w.vocab,
-                         num_splits=splits)
+                         max_seq_len=cap, num_pages=cache["num_pages"], vocab=w.vocab,
+                         num_splits=splits, min_seq_len_bound=len0)
     stream = torch.cuda.current_stream()
     call_events = []
 
     def run_step(i, record):
+        # the host's own upper bound on the lengths: initial maximum plus K tokens per step so far
+        # (no device round trip); it sizes the attention grid of this step
+        step.set_max_seq_len(min(cap, len0 + (i if w.vocab else 0) * K))
         d, a = sets[i % N_SETS]
         ev = None
         if record:

@@ -30,7 +30,7 @@ class DecodeStep:
 
     def __init__(self, *, batch, num_q_heads, num_kv_heads, head_dim, block_k, page_size, max_pages_per_seq,
                  max_seq_len, num_pages, vocab=0, num_layers=1, num_splits=0, sm_scale=None, device=0,
-                 pool_strides=None):
+                 pool_strides=None, min_seq_len_bound=None):
         if not torch.cuda.is_available():
             raise RuntimeError("paper_2605_12825_amd needs a HIP device; there is no CPU path")
         self.device = torch.device("cuda", device)
@@ -45,12 +45,27 @@ class DecodeStep:
                                     vocab=vocab, sm_scale=sm_scale, **kw)
         self.ctx = B.orthrus_create(device)
         self.num_splits = B.orthrus_attn_num_splits(self.params)
+        # workspace for every host bound on the lengths the caller may set later (see set_max_seq_len)
         n = B.orthrus_attn_workspace_bytes(self.params)
+        lo = max_seq_len if min_seq_len_bound is None else min_seq_len_bound
+        for bound in range(lo, max_seq_len, max(block_k, 1)):
+            self.params.max_seq_len = bound
+            n = max(n, B.orthrus_attn_workspace_bytes(self.params))
+        self.params.max_seq_len = max_seq_len
         self.attn_ws = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
         self.cons_ws = None
         if vocab > 0:
             n = B.orthrus_consensus_workspace_bytes(self.params)
             self.cons_ws = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
+
+    def set_max_seq_len(self, bound: int) -> None:
+        """Tightens the host upper bound on the sequence lengths (it sizes the attention grid).
+
+        `bound` must lie between the `min_seq_len_bound` and the `max_seq_len` given at construction,
+        and must not be below any current sequence length.
+        """
+        self.params.max_seq_len = int(bound)
+        self.num_splits = B.orthrus_attn_num_splits(self.params)
 
     def close(self):
         if self.ctx:
