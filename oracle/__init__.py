@@ -50,6 +50,10 @@ def _load():
         lib.orthrus_oracle_consensus_commit.argtypes = [
             i32, i32, i32, i32, i32, i32, i32, i32, i64,
             p, p, p, p, p, p, i64, i64, i64, i64, p, p, p, p, p, p]
+        lib.orthrus_oracle_sampling_consensus_commit.restype = ctypes.c_int
+        lib.orthrus_oracle_sampling_consensus_commit.argtypes = [
+            i32, i32, i32, f64, i32, i32, i32, i32, i32, i64,
+            p, p, p, p, p, p, p, p, p, i64, i64, i64, i64, p, p, p, p, p, p, p, p]
         _lib = lib
     return _lib
 
@@ -148,3 +152,52 @@ def consensus_commit(ar_logits: np.ndarray, draft_tokens: np.ndarray,
         raise RuntimeError("orthrus_oracle_consensus_commit failed with status %d" % rc)
     return dict(accept_len=accept_len, num_committed=num_committed, out_tokens=out_tokens,
                 next_anchor=next_anchor, status=rc)
+
+
+def sampling_consensus_commit(ar_logits: np.ndarray, diff_logits: np.ndarray, draft_tokens: np.ndarray,
+                              accept_u: np.ndarray, gumbel: np.ndarray, temperature: float,
+                              k_blk_ar: Optional[np.ndarray] = None, v_blk_ar: Optional[np.ndarray] = None,
+                              k_pool: Optional[np.ndarray] = None, v_pool: Optional[np.ndarray] = None,
+                              page_table: Optional[np.ndarray] = None, seq_lens: Optional[np.ndarray] = None,
+                              allow_capacity_error: bool = False) -> Dict[str, np.ndarray]:
+    """Temperature > 0 consensus (speculative-sampling accept/replace rule) plus in-place commit.
+
+    Shapes as in ``consensus_commit``; ``diff_logits`` like ``ar_logits``; ``accept_u`` is ``[B,K]``
+    fp32 in [0,1), ``gumbel`` is ``[B,V]`` fp32 standard Gumbel noise.  Also returns the decision
+    margins the oracle reports (``margin_accept [B,K]``, ``margin_draw [B]``).
+    """
+    lib = _load()
+    B, K, V = ar_logits.shape
+    for a, n in ((ar_logits, "ar_logits"), (diff_logits, "diff_logits"), (accept_u, "accept_u"), (gumbel, "gumbel")):
+        _check(a, np.float32, n)
+    _check(draft_tokens, np.int32, "draft_tokens")
+    if diff_logits.shape != (B, K, V) or accept_u.shape != (B, K) or gumbel.shape != (B, V):
+        raise ValueError("sampling input shape mismatch")
+    accept_len = np.empty(B, np.int32); num_committed = np.empty(B, np.int32)
+    out_tokens = np.empty((B, K), np.int32); next_anchor = np.empty(B, np.int32)
+    m_acc = np.empty((B, K), np.float64); m_draw = np.empty(B, np.float64)
+    if k_blk_ar is None:
+        rc = lib.orthrus_oracle_sampling_consensus_commit(
+            B, K, V, float(temperature), 0, 0, 0, 0, 0, 0, _ptr(ar_logits), _ptr(diff_logits),
+            _ptr(draft_tokens), _ptr(accept_u), _ptr(gumbel), None, None, None, None, 0, 0, 0, 0, None, None,
+            _ptr(accept_len), _ptr(num_committed), _ptr(out_tokens), _ptr(next_anchor), _ptr(m_acc), _ptr(m_draw))
+    else:
+        kb = k_blk_ar if k_blk_ar.ndim == 5 else k_blk_ar[None]
+        vb = v_blk_ar if v_blk_ar.ndim == 5 else v_blk_ar[None]
+        kp = k_pool if k_pool.ndim == 5 else k_pool[None]
+        vp = v_pool if v_pool.ndim == 5 else v_pool[None]
+        for a, n in ((kb, "k_blk_ar"), (vb, "v_blk_ar"), (kp, "k_pool"), (vp, "v_pool")):
+            _check(a, np.uint16, n)
+        _check(page_table, np.int32, "page_table"); _check(seq_lens, np.int32, "seq_lens")
+        layers, _, _, Hkv, d = kb.shape
+        es = kp.itemsize
+        sl, sp, sh, st = (kp.strides[0] // es, kp.strides[1] // es, kp.strides[2] // es, kp.strides[3] // es)
+        rc = lib.orthrus_oracle_sampling_consensus_commit(
+            B, K, V, float(temperature), layers, Hkv, d, kp.shape[3], page_table.shape[1], kp.shape[1],
+            _ptr(ar_logits), _ptr(diff_logits), _ptr(draft_tokens), _ptr(accept_u), _ptr(gumbel),
+            _ptr(kb), _ptr(vb), _ptr(kp), _ptr(vp), sl, sp, sh, st, _ptr(page_table), _ptr(seq_lens),
+            _ptr(accept_len), _ptr(num_committed), _ptr(out_tokens), _ptr(next_anchor), _ptr(m_acc), _ptr(m_draw))
+    if rc != 0 and not (rc == -4 and allow_capacity_error):
+        raise RuntimeError("orthrus_oracle_sampling_consensus_commit failed with status %d" % rc)
+    return dict(accept_len=accept_len, num_committed=num_committed, out_tokens=out_tokens,
+                next_anchor=next_anchor, status=rc, margin_accept=m_acc, margin_draw=m_draw)

@@ -22,6 +22,12 @@
  *                                     correction, cache ends at step t+j); Fig. 2(b)
  *                                     (accepted tokens' KV appended to the shared cache).
  *
+ *   orthrus_oracle_sampling_consensus Section 3.3, the sentence on temperature T > 0: exact rejection
+ *                                     sampling after the cited speculative-sampling rule (a draft x
+ *                                     drawn from q is kept with probability min(1, p(x)/q(x)); a
+ *                                     rejected one is replaced by a draw from the normalised positive
+ *                                     part of p - q), applied left to right over the block.
+ *
  * Readings taken where the paper is silent (each is a stated reading, not a derivation):
  *   - the cache holds tokens strictly before the anchor x_t (Section 3.3: K_AR^{<t}); the
  *     anchor's own K/V is in-block row 0;
@@ -250,5 +256,145 @@ int orthrus_oracle_consensus_commit(
         seq_lens[b] = L + m;
     }
     free(am);
+    return status;
+}
+
+/*
+ * Lossless sampling consensus for temperature T > 0 (Section 3.3; the accept/replace rule is the
+ * published speculative-sampling rule the paper cites, restated here):
+ *   p_k = softmax(ar_logits[b,k,:] / T)     target distribution of block row k (AR view)
+ *   q_k = softmax(diff_logits[b,k,:] / T)   distribution the draft token of row k was drawn from
+ *   for k = 0, 1, ...: x = draft[b,k]; keep x iff  accept_u[b,k] * q_k(x) < p_k(x)
+ *                      (probability min(1, p/q) for a uniform accept_u in [0,1); an x outside [0,V)
+ *                      is never kept)
+ *   at the first row j that is not kept, the emitted token is a draw from r = max(0, p_j - q_j)
+ *   normalised, taken as  argmax_v [ log r(v) + gumbel[b,v] ]  (exact categorical sampling when
+ *   gumbel holds independent standard Gumbel noise; smallest index on ties); if r is zero
+ *   everywhere the draw is from p_j instead.
+ *   n_acc = j (K if every draft is kept), m = min(n_acc + 1, K) tokens are emitted: the kept drafts,
+ *   then the replacement when j < K.  Outputs and the commit are as in the greedy oracle.
+ * All random numbers are inputs (accept_u [B,K], gumbel [B,V]); nothing is drawn here.
+ * margin_accept [B,K] / margin_draw [B] (optional, may be NULL) report how far each decision was from
+ * flipping: |log(u q(x)) - log p(x)| for the rows that were examined (0 for an out-of-range x, -1 for
+ * rows not examined), and the gap between the best and second-best score of the draw (-1 if none).
+ */
+int orthrus_oracle_sampling_consensus_commit(
+    int batch, int block_k, int vocab, double temperature, int num_layers, int num_kv_heads, int head_dim,
+    int page_size, int max_pages_per_seq, int64_t num_pages,
+    const float *ar_logits, const float *diff_logits, const int32_t *draft_tokens,
+    const float *accept_u, const float *gumbel,
+    const uint16_t *k_blk_ar, const uint16_t *v_blk_ar,
+    uint16_t *k_pool, uint16_t *v_pool,
+    int64_t stride_layer, int64_t stride_page, int64_t stride_head, int64_t stride_tok,
+    const int32_t *page_table, int32_t *seq_lens,
+    int32_t *accept_len, int32_t *num_committed, int32_t *out_tokens, int32_t *next_anchor,
+    double *margin_accept, double *margin_draw)
+{
+    if (batch < 0 || block_k <= 0 || vocab <= 0 || !(temperature > 0.0)) return -1;
+    const int K = block_k, V = vocab;
+    const int do_commit = (k_blk_ar != NULL && v_blk_ar != NULL);
+    if (do_commit && (num_layers <= 0 || num_kv_heads <= 0 || head_dim <= 0 || page_size <= 0)) return -1;
+    int status = 0;
+    double *lp = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lq = (double *)malloc(sizeof(double) * (size_t)V);
+    if (!lp || !lq) { free(lp); free(lq); return -1; }
+
+    for (int b = 0; b < batch; ++b) {
+        int n_acc = K;
+        int replacement = -1;
+        if (margin_draw) margin_draw[b] = -1.0;
+        for (int k = 0; k < K; ++k)
+            if (margin_accept) margin_accept[(int64_t)b * K + k] = -1.0;
+        for (int k = 0; k < K; ++k) {
+            const float *pr = ar_logits + ((int64_t)b * K + k) * V;
+            const float *qr = diff_logits + ((int64_t)b * K + k) * V;
+            /* log-softmax of both rows at temperature T (two passes: max, then log-sum-exp) */
+            double mp = -INFINITY, mq = -INFINITY;
+            for (int v = 0; v < V; ++v) {
+                lp[v] = (double)pr[v] / temperature;
+                lq[v] = (double)qr[v] / temperature;
+                if (lp[v] > mp) mp = lp[v];
+                if (lq[v] > mq) mq = lq[v];
+            }
+            double sp = 0.0, sq = 0.0;
+            for (int v = 0; v < V; ++v) { sp += exp(lp[v] - mp); sq += exp(lq[v] - mq); }
+            const double lsep = mp + log(sp), lseq = mq + log(sq);
+            const int32_t x = draft_tokens[(int64_t)b * K + k];
+            int keep = 0;
+            if (x >= 0 && x < V) {
+                const double px = exp(lp[x] - lsep), qx = exp(lq[x] - lseq);
+                const double u = (double)accept_u[(int64_t)b * K + k];
+                keep = (u * qx < px);
+                if (margin_accept) {
+                    const double a = log(u * qx), c = log(px);   /* -inf when a factor is zero */
+                    margin_accept[(int64_t)b * K + k] = (isinf(a) && isinf(c)) ? 0.0 : fabs(a - c);
+                }
+            } else if (margin_accept) {
+                margin_accept[(int64_t)b * K + k] = 0.0;
+            }
+            if (keep) continue;
+            /* first rejection: draw the replacement from the positive part of p - q */
+            n_acc = k;
+            double best = -INFINITY, second = -INFINITY;
+            int best_v = -1, any = 0;
+            for (int v = 0; v < V; ++v) {
+                const double r = exp(lp[v] - lsep) - exp(lq[v] - lseq);
+                if (r > 0.0) any = 1;
+            }
+            for (int v = 0; v < V; ++v) {
+                double w;
+                if (any) {
+                    const double r = exp(lp[v] - lsep) - exp(lq[v] - lseq);
+                    if (!(r > 0.0)) continue;
+                    w = log(r);
+                } else {
+                    w = lp[v] - lsep;
+                }
+                const double score = w + (double)gumbel[(int64_t)b * V + v];
+                if (score > best) { second = best; best = score; best_v = v; }
+                else if (score > second) second = score;
+            }
+            replacement = best_v;
+            if (margin_draw) margin_draw[b] = isinf(second) ? INFINITY : best - second;
+            break;
+        }
+        const int m = (n_acc + 1 < K) ? n_acc + 1 : K;
+        accept_len[b] = n_acc;
+        for (int k = 0; k < K; ++k) {
+            int32_t t = -1;
+            if (k < n_acc) t = draft_tokens[(int64_t)b * K + k];
+            else if (k == n_acc && k < m) t = replacement;
+            out_tokens[(int64_t)b * K + k] = (k < m) ? t : -1;
+        }
+        next_anchor[b] = out_tokens[(int64_t)b * K + m - 1];
+        num_committed[b] = m;
+        if (!do_commit) continue;
+
+        const int L = seq_lens[b];
+        int mapped = (L >= 0);
+        for (int k = 0; k < m && mapped; ++k) {
+            int slot = (L + k) / page_size;
+            if (slot >= max_pages_per_seq) { mapped = 0; break; }
+            int32_t pg = page_table[(int64_t)b * max_pages_per_seq + slot];
+            if (pg < 0 || pg >= num_pages) mapped = 0;
+        }
+        if (!mapped) { num_committed[b] = 0; status = -4; continue; }
+        for (int k = 0; k < m; ++k) {
+            const int pos = L + k;
+            const int32_t pg = page_table[(int64_t)b * max_pages_per_seq + pos / page_size];
+            for (int layer = 0; layer < num_layers; ++layer) {
+                for (int g = 0; g < num_kv_heads; ++g) {
+                    int64_t dst = (int64_t)layer * stride_layer + (int64_t)pg * stride_page +
+                                  (int64_t)g * stride_head + (int64_t)(pos % page_size) * stride_tok;
+                    int64_t src = ((((int64_t)layer * batch + b) * K + k) * num_kv_heads + g) * head_dim;
+                    memcpy(k_pool + dst, k_blk_ar + src, sizeof(uint16_t) * (size_t)head_dim);
+                    memcpy(v_pool + dst, v_blk_ar + src, sizeof(uint16_t) * (size_t)head_dim);
+                }
+            }
+        }
+        seq_lens[b] = L + m;
+    }
+    free(lp);
+    free(lq);
     return status;
 }

@@ -12,10 +12,11 @@ from .generate import (
     make_cache,
     make_block,
     make_consensus_case,
+    make_sampling_case,
     make_step_inputs,
 )
 
 __all__ = [
     "Workload", "WORKLOADS", "get_workload", "f32_to_bf16_bits", "bf16_bits_to_f32",
-    "make_cache", "make_block", "make_consensus_case", "make_step_inputs",
+    "make_cache", "make_block", "make_consensus_case", "make_sampling_case", "make_step_inputs",
 ]

@@ -148,6 +148,35 @@ def make_consensus_case(w: Workload, seed: int, vocab: Optional[int] = None,
     return dict(ar_logits=logits, draft_tokens=draft, planted_top=top, planted_n_acc=n_acc)
 
 
+def make_sampling_case(w: Workload, seed: int, vocab: Optional[int] = None, temperature: float = 1.0,
+                       divergence: float = 0.5, logit_scale: float = 2.0) -> Dict[str, np.ndarray]:
+    """Inputs of the temperature > 0 consensus: target and draft logits, drafts, and the random numbers.
+
+    ar_logits ~ logit_scale * N(0,1); diff_logits = ar_logits + divergence * N(0,1) (a draft
+    distribution close to, but not equal to, the target); each draft token is drawn from
+    softmax(diff_logits / temperature) by perturbing the scaled logits with Gumbel noise and taking the
+    largest (the way a sampler outside the path would produce it); accept_u ~ U[0,1) and one row of
+    standard Gumbel noise per sequence are the random numbers the consensus step consumes.
+    """
+    rng = np.random.default_rng(seed)
+    V = int(vocab if vocab is not None else w.vocab)
+    B, K = w.batch, w.block_k
+    ar = np.empty((B, K, V), dtype=np.float32)
+    df = np.empty((B, K, V), dtype=np.float32)
+    draft = np.empty((B, K), dtype=np.int32)
+    for b in range(B):
+        for k in range(K):
+            a = rng.standard_normal(V, dtype=np.float32) * np.float32(logit_scale)
+            ar[b, k] = a
+            df[b, k] = a + rng.standard_normal(V, dtype=np.float32) * np.float32(divergence)
+            noise = rng.gumbel(size=V)
+            draft[b, k] = int(np.argmax(df[b, k].astype(np.float64) / temperature + noise))
+    accept_u = rng.random((B, K), dtype=np.float32)
+    gumbel = rng.gumbel(size=(B, V)).astype(np.float32)
+    return dict(ar_logits=ar, diff_logits=df, draft_tokens=draft, accept_u=accept_u, gumbel=gumbel,
+                temperature=float(temperature))
+
+
 def make_step_inputs(w: Workload, step: int = 0, value_scale: float = 1.0,
                      with_cache: bool = True) -> Dict[str, np.ndarray]:
     """All inputs of one decode step: cache (step 0 only), both views' blocks, consensus case."""
