@@ -91,6 +91,7 @@ const char *orthrus_status_string(orthrus_status s);
  */
 int64_t orthrus_attn_workspace_bytes(const orthrus_params *p);
 int64_t orthrus_consensus_workspace_bytes(const orthrus_params *p);
+int64_t orthrus_sampling_workspace_bytes(const orthrus_params *p);
 /* Number of KV splits the attention call will use for these params (>= 1), or a negative status. */
 int32_t orthrus_attn_num_splits(const orthrus_params *p);
 
@@ -165,6 +166,43 @@ orthrus_status orthrus_consensus_commit(orthrus_ctx *ctx, const orthrus_params *
                                         int32_t *accept_len, int32_t *num_committed,
                                         int32_t *out_tokens, int32_t *next_anchor,
                                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Lossless consensus for temperature T > 0 and commit — Section 3.3, the sentence on diverse
+ * generation: exact rejection sampling that aligns the diffusion view's drafts with the AR
+ * distribution.  The accept/replace rule is the published speculative-sampling rule the paper cites:
+ * with p_k = softmax(ar_logits[b][k] / T) and q_k = softmax(diff_logits[b][k] / T), the draft x of row
+ * k (drawn from q_k by the caller) is kept iff accept_u[b][k] * q_k(x) < p_k(x), rows are examined left
+ * to right, and at the first row j that is not kept the emitted token is
+ *   argmax_v [ log max(0, p_j(v) - q_j(v)) + gumbel[b][v] ]   (smallest index on ties),
+ * i.e. a draw from the normalised positive part of p_j - q_j when gumbel holds independent standard
+ * Gumbel noise (from p_j itself if that part is empty).  accept_len[b] = j (K if every draft is kept),
+ * num_committed[b] = m = min(j + 1, K); out_tokens[b] = the kept drafts, then the replacement when
+ * j < K, then -1; next_anchor[b] = the last emitted token.  Cache commit, length update and the
+ * device-side capacity error are exactly those of orthrus_consensus_commit.
+ * Every random number is an argument, so the call is a deterministic function of its inputs.
+ *
+ *   temperature  [host value] T > 0, applied to both logit sets
+ *   ar_logits, diff_logits [dev] fp32 [B, K, V]
+ *   draft_tokens [dev] int32 [B, K]        a value outside [0, V) is never kept
+ *   accept_u     [dev] fp32 [B, K]         uniforms in [0, 1)
+ *   gumbel       [dev] fp32 [B, V]         standard Gumbel noise for the replacement draw
+ *   remaining arguments as in orthrus_consensus_commit; workspace at least
+ *   orthrus_sampling_workspace_bytes(p)
+ *
+ * Arithmetic is fp32 (log-sum-exp per 8192-element chunk, merged in chunk order); a decision whose
+ * two sides differ by less than fp32 rounding of the log-sum-exp may fall either way.
+ */
+orthrus_status orthrus_sampling_consensus_commit(orthrus_ctx *ctx, const orthrus_params *p, float temperature,
+                                                 const float *ar_logits, const float *diff_logits,
+                                                 const int32_t *draft_tokens, const float *accept_u,
+                                                 const float *gumbel,
+                                                 const void *k_blk_ar, const void *v_blk_ar,
+                                                 void *k_pool, void *v_pool,
+                                                 const int32_t *page_table, int32_t *seq_lens,
+                                                 int32_t *accept_len, int32_t *num_committed,
+                                                 int32_t *out_tokens, int32_t *next_anchor,
+                                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Synchronises `stream`, copies the context's device error word to *code [host] (ORTHRUS_OK or

@@ -25,8 +25,9 @@ ORTHRUS_VIEW_AR_VERIFY = 1
 
 EXPORTED = [
     "orthrus_create", "orthrus_destroy", "orthrus_status_string", "orthrus_attn_workspace_bytes",
-    "orthrus_consensus_workspace_bytes", "orthrus_attn_num_splits", "orthrus_dual_view_attn",
-    "orthrus_consensus_commit", "orthrus_last_device_error",
+    "orthrus_consensus_workspace_bytes", "orthrus_sampling_workspace_bytes", "orthrus_attn_num_splits",
+    "orthrus_dual_view_attn", "orthrus_consensus_commit", "orthrus_sampling_consensus_commit",
+    "orthrus_last_device_error",
 ]
 
 
@@ -74,6 +75,11 @@ def _load() -> ctypes.CDLL:
     lib.orthrus_consensus_commit.restype = ctypes.c_int
     lib.orthrus_consensus_commit.argtypes = [vp, pp, vp, i32p, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, i32p,
                                              vp, ctypes.c_size_t, vp]
+    lib.orthrus_sampling_workspace_bytes.restype = ctypes.c_int64
+    lib.orthrus_sampling_workspace_bytes.argtypes = [pp]
+    lib.orthrus_sampling_consensus_commit.restype = ctypes.c_int
+    lib.orthrus_sampling_consensus_commit.argtypes = [vp, pp, ctypes.c_float, vp, vp, i32p, vp, vp, vp, vp, vp, vp,
+                                                      i32p, i32p, i32p, i32p, i32p, i32p, vp, ctypes.c_size_t, vp]
     lib.orthrus_last_device_error.restype = ctypes.c_int
     lib.orthrus_last_device_error.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
     return lib
@@ -167,6 +173,27 @@ def orthrus_consensus_commit(ctx, p: orthrus_params, ar_logits, draft_tokens, k_
                                        _stream_handle(stream))
     if check and st != ORTHRUS_OK:
         raise OrthrusError(st, "orthrus_consensus_commit")
+    return st
+
+
+def orthrus_sampling_workspace_bytes(p: orthrus_params) -> int:
+    n = _lib.orthrus_sampling_workspace_bytes(ctypes.byref(p))
+    if n < 0:
+        raise OrthrusError(int(n), "orthrus_sampling_workspace_bytes")
+    return int(n)
+
+
+def orthrus_sampling_consensus_commit(ctx, p: orthrus_params, temperature: float, ar_logits, diff_logits,
+                                      draft_tokens, accept_u, gumbel, k_blk_ar, v_blk_ar, k_pool, v_pool,
+                                      page_table, seq_lens, accept_len, num_committed, out_tokens, next_anchor,
+                                      workspace=None, stream=None, check: bool = True) -> int:
+    st = _lib.orthrus_sampling_consensus_commit(
+        ctx, ctypes.byref(p), float(temperature), _ptr(ar_logits), _ptr(diff_logits), _ptr(draft_tokens),
+        _ptr(accept_u), _ptr(gumbel), _ptr(k_blk_ar), _ptr(v_blk_ar), _ptr(k_pool), _ptr(v_pool), _ptr(page_table),
+        _ptr(seq_lens), _ptr(accept_len), _ptr(num_committed), _ptr(out_tokens), _ptr(next_anchor),
+        _ptr(workspace), _nbytes(workspace), _stream_handle(stream))
+    if check and st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_sampling_consensus_commit")
     return st
 
 

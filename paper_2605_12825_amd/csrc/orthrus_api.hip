@@ -248,6 +248,77 @@ orthrus_status orthrus_consensus_commit(orthrus_ctx *ctx, const orthrus_params *
     return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
 }
 
+int64_t orthrus_sampling_workspace_bytes(const orthrus_params *p)
+{
+    orthrus_status s = check_params(p, false, true, false);
+    if (s != ORTHRUS_OK) return (int64_t)s;
+    const size_t rows = (size_t)p->batch * p->block_k;
+    const size_t chunks = (size_t)consensus_chunks(p);
+    return (int64_t)(align_up(rows * chunks * 16, 256) + align_up((size_t)p->batch * chunks * 16, 256) +
+                     align_up((size_t)p->batch * 2 * sizeof(int32_t), 256));
+}
+
+orthrus_status orthrus_sampling_consensus_commit(orthrus_ctx *ctx, const orthrus_params *p, float temperature,
+                                                 const float *ar_logits, const float *diff_logits,
+                                                 const int32_t *draft_tokens, const float *accept_u,
+                                                 const float *gumbel,
+                                                 const void *k_blk_ar, const void *v_blk_ar,
+                                                 void *k_pool, void *v_pool,
+                                                 const int32_t *page_table, int32_t *seq_lens,
+                                                 int32_t *accept_len, int32_t *num_committed,
+                                                 int32_t *out_tokens, int32_t *next_anchor,
+                                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx) return ORTHRUS_EINVAL;
+    if ((k_blk_ar == nullptr) != (v_blk_ar == nullptr)) return ORTHRUS_EINVAL;
+    const bool do_commit = k_blk_ar != nullptr;
+    orthrus_status s = check_params(p, false, true, do_commit);
+    if (s != ORTHRUS_OK) return s;
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) return ORTHRUS_EINVAL;
+    if (!ar_logits || !diff_logits || !draft_tokens || !accept_u || !gumbel || !accept_len || !num_committed ||
+        !out_tokens || !next_anchor)
+        return ORTHRUS_EINVAL;
+    if ((((uintptr_t)ar_logits) | ((uintptr_t)diff_logits) | ((uintptr_t)gumbel) | ((uintptr_t)accept_u)) & 3)
+        return ORTHRUS_EINVAL;
+    if (do_commit) {
+        if (!k_pool || !v_pool || !page_table || !seq_lens || p->num_layers <= 0) return ORTHRUS_EINVAL;
+        if (p->num_layers > 65535) return ORTHRUS_EUNSUPPORTED;
+        const uintptr_t al = (uintptr_t)k_blk_ar | (uintptr_t)v_blk_ar | (uintptr_t)k_pool | (uintptr_t)v_pool;
+        if (al & 15) return ORTHRUS_EINVAL;
+    }
+    if (p->batch == 0) return ORTHRUS_OK;
+    const size_t rows = (size_t)p->batch * p->block_k;
+    const size_t chunks = (size_t)consensus_chunks(p);
+    if (rows * chunks > 0x7fffffffull || chunks > 65535) return ORTHRUS_EUNSUPPORTED;
+    const size_t o1 = align_up(rows * chunks * 16, 256);
+    const size_t o2 = o1 + align_up((size_t)p->batch * chunks * 16, 256);
+    const size_t need = o2 + align_up((size_t)p->batch * 2 * sizeof(int32_t), 256);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return ORTHRUS_EWORKSPACE;
+
+    orthrus::SamplingArgs a;
+    orthrus::ConsensusArgs &c = a.c;
+    c.ar_logits = ar_logits; c.draft_tokens = draft_tokens;
+    c.k_blk_ar = (const uint16_t *)k_blk_ar; c.v_blk_ar = (const uint16_t *)v_blk_ar;
+    c.k_pool = (uint16_t *)k_pool; c.v_pool = (uint16_t *)v_pool;
+    c.page_table = page_table; c.seq_lens = seq_lens;
+    c.accept_len = accept_len; c.num_committed = num_committed; c.out_tokens = out_tokens; c.next_anchor = next_anchor;
+    c.part_val = nullptr; c.part_idx = nullptr;
+    c.commit_info = (int32_t *)((char *)workspace + o2);
+    c.err_word = ctx->err_word;
+    c.stride_layer = p->pool_stride_layer; c.stride_page = p->pool_stride_page;
+    c.stride_head = p->pool_stride_head; c.stride_tok = p->pool_stride_tok; c.num_pages = p->num_pages;
+    c.batch = p->batch; c.block_k = p->block_k; c.vocab = p->vocab; c.num_layers = p->num_layers;
+    c.num_kv_heads = p->num_kv_heads; c.head_dim = p->head_dim;
+    c.page_shift = do_commit ? log2_exact(p->page_size) : 0; c.max_pages_per_seq = p->max_pages_per_seq;
+    c.chunks = (int)chunks; c.chunk_elems = orthrus::consensus_chunk_elems(); c.do_commit = do_commit ? 1 : 0;
+    a.diff_logits = diff_logits; a.accept_u = accept_u; a.gumbel = gumbel;
+    a.lse_part = (float4 *)workspace;
+    a.draw_part = (float4 *)((char *)workspace + o1);
+    a.inv_temperature = 1.0f / temperature;
+    hipError_t e = orthrus::launch_sampling_consensus(a, (hipStream_t)stream);
+    return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
 orthrus_status orthrus_last_device_error(orthrus_ctx *ctx, void *stream, int32_t *code)
 {
     if (!ctx || !code) return ORTHRUS_EINVAL;

@@ -48,11 +48,22 @@ struct ConsensusArgs {
     int page_shift, max_pages_per_seq, chunks, chunk_elems, do_commit;
 };
 
+struct SamplingArgs {
+    ConsensusArgs c;          // shared fields (ar_logits, drafts, pools, outputs, commit_info, err_word, shapes)
+    const float *diff_logits; // [B][K][V]
+    const float *accept_u;    // [B][K]
+    const float *gumbel;      // [B][V]
+    float4 *lse_part;         // [B*K][chunks]: (max_p, sum_p, max_q, sum_q) of logits / T over the chunk
+    float4 *draw_part;        // [B][chunks]: (best score among p>q, its index, best score of log p + g, its index)
+    float inv_temperature;
+};
+
 // Host-side launchers (defined next to the kernels).  Return hipSuccess or the launch error.
 hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv_heads, int max_seq_len,
                      int requested_splits, int num_cus, AttnPlan *plan);
 hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream);
 hipError_t launch_consensus(const ConsensusArgs &a, hipStream_t stream);
+hipError_t launch_sampling_consensus(const SamplingArgs &a, hipStream_t stream);
 int consensus_chunk_elems();
 
 }  // namespace orthrus

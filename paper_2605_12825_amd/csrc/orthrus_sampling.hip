@@ -1,0 +1,286 @@
+// Lossless consensus for temperature T > 0 on gfx950 (Section 3.3: exact rejection sampling after the
+// speculative-sampling rule the paper cites): with p_k = softmax(ar_logits[k] / T) and
+// q_k = softmax(diff_logits[k] / T), draft x of row k is kept iff accept_u[k] * q_k(x) < p_k(x); at the
+// first row j that is not kept the emitted token is argmax_v [ log max(0, p_j - q_j)(v) + gumbel(v) ]
+// (a draw from the normalised positive part of p_j - q_j; from p_j if that part is empty).  All random
+// numbers are inputs, so the step is a deterministic function of its arguments.
+//
+//   lse_partial_kernel      grid (row * chunks + chunk): (max, sum of exp) of both scaled logit rows
+//                           over one 8192-element chunk, 16-byte loads, wavefront shuffles.
+//   draw_partial_kernel     grid (chunk, sequence): every workgroup re-derives the K keep decisions of
+//                           its sequence from the chunk pairs (same code, same order => same answer
+//                           everywhere), and if a row j < K was rejected scans its chunk of row j for the
+//                           two candidate maxima.
+//   sample_commit_kernel    grid (sequence): decisions again, final maximum over the chunks in chunk
+//                           order, outputs, page check and the in-place commit of the kept rows.
+#include "orthrus_internal.h"
+
+namespace orthrus {
+
+constexpr int kSChunk = 8192;
+constexpr int kSInlineLayers = 2;
+
+__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2)
+{
+    const float mn = fmaxf(m, m2);
+    if (mn == -INFINITY) { m = mn; s = 0.f; return; }
+    s = s * expf(m - mn) + s2 * expf(m2 - mn);
+    m = mn;
+}
+
+__global__ void __launch_bounds__(256) lse_partial_kernel(const SamplingArgs a)
+{
+    const int chunks = a.c.chunks, V = a.c.vocab;
+    const int row = blockIdx.x / chunks, chunk = blockIdx.x - row * chunks;
+    const int tid = threadIdx.x;
+    const float *pr = a.c.ar_logits + (int64_t)row * V;
+    const float *qr = a.diff_logits + (int64_t)row * V;
+    const int begin = chunk * kSChunk, end = min(V, begin + kSChunk);
+    const float it = a.inv_temperature;
+    constexpr int PER = kSChunk / 256;  // 32 values per thread and row
+    float xp[PER], xq[PER];
+    const bool vec_ok = ((V & 3) == 0) && (((((uintptr_t)a.c.ar_logits) | ((uintptr_t)a.diff_logits)) & 15) == 0);
+    float mp = -INFINITY, mq = -INFINITY;
+    if (vec_ok) {
+#pragma unroll
+        for (int u = 0; u < PER / 4; ++u) {
+            const int i = begin + (u * 256 + tid) * 4;
+            float4 vp = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY), vq = vp;
+            if (i < end) { vp = *(const float4 *)(pr + i); vq = *(const float4 *)(qr + i); }
+            xp[4 * u] = vp.x * it; xp[4 * u + 1] = vp.y * it; xp[4 * u + 2] = vp.z * it; xp[4 * u + 3] = vp.w * it;
+            xq[4 * u] = vq.x * it; xq[4 * u + 1] = vq.y * it; xq[4 * u + 2] = vq.z * it; xq[4 * u + 3] = vq.w * it;
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int i = begin + u * 256 + tid;
+            xp[u] = i < end ? pr[i] * it : -INFINITY;
+            xq[u] = i < end ? qr[i] * it : -INFINITY;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) { mp = fmaxf(mp, xp[u]); mq = fmaxf(mq, xq[u]); }
+    float sp = 0.f, sq = 0.f;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        sp += (xp[u] == -INFINITY) ? 0.f : expf(xp[u] - mp);
+        sq += (xq[u] == -INFINITY) ? 0.f : expf(xq[u] - mq);
+    }
+    // wavefront, then workgroup merge in a fixed order
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        lse_merge(mp, sp, __shfl_xor(mp, off), __shfl_xor(sp, off));
+        lse_merge(mq, sq, __shfl_xor(mq, off), __shfl_xor(sq, off));
+    }
+    __shared__ float4 sh[4];
+    if ((tid & 63) == 0) sh[tid >> 6] = make_float4(mp, sp, mq, sq);
+    __syncthreads();
+    if (tid == 0) {
+        float4 r = sh[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) { lse_merge(r.x, r.y, sh[w].x, sh[w].y); lse_merge(r.z, r.w, sh[w].z, sh[w].w); }
+        a.lse_part[(int64_t)row * chunks + chunk] = r;
+    }
+}
+
+// Keep decisions of sequence b, made by the first wavefront (lane k < K owns row k).  Returns the first
+// row that is not kept (K if none) and, for that row, the two log-sum-exps.
+__device__ __forceinline__ int first_rejected(const SamplingArgs &a, int b, int lane, float &lsep_j, float &lseq_j)
+{
+    const int K = a.c.block_k, V = a.c.vocab, chunks = a.c.chunks;
+    bool keep = true;  // lanes >= K do not stop the run
+    float lsep = 0.f, lseq = 0.f;
+    if (lane < K) {
+        const int64_t row = (int64_t)b * K + lane;
+        float4 r = a.lse_part[row * chunks];
+        for (int ch = 1; ch < chunks; ++ch) {
+            const float4 t = a.lse_part[row * chunks + ch];
+            lse_merge(r.x, r.y, t.x, t.y);
+            lse_merge(r.z, r.w, t.z, t.w);
+        }
+        lsep = r.x + logf(r.y);
+        lseq = r.z + logf(r.w);
+        const int x = a.c.draft_tokens[row];
+        keep = false;
+        if (x >= 0 && x < V) {
+            const float px = expf(a.c.ar_logits[row * V + x] * a.inv_temperature - lsep);
+            const float qx = expf(a.diff_logits[row * V + x] * a.inv_temperature - lseq);
+            keep = a.accept_u[row] * qx < px;
+        }
+    }
+    const unsigned long long rej = ~__ballot(keep);
+    const int j = rej ? __ffsll((long long)rej) - 1 : 64;
+    const int jj = j < K ? j : K;
+    lsep_j = __shfl(lsep, jj < K ? jj : 0);
+    lseq_j = __shfl(lseq, jj < K ? jj : 0);
+    return jj;
+}
+
+__device__ __forceinline__ bool better_score(float v1, int i1, float v2, int i2)
+{
+    return v1 > v2 || (v1 == v2 && i1 < i2);
+}
+
+__global__ void __launch_bounds__(256) draw_partial_kernel(const SamplingArgs a)
+{
+    const int chunk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int K = a.c.block_k, V = a.c.vocab, chunks = a.c.chunks;
+    __shared__ int s_j;
+    __shared__ float s_lsep, s_lseq;
+    if (tid < 64) {
+        float lp, lq;
+        const int j = first_rejected(a, b, tid, lp, lq);
+        if (tid == 0) { s_j = j; s_lsep = lp; s_lseq = lq; }
+    }
+    __syncthreads();
+    const int j = s_j;
+    if (j >= K) return;  // every draft kept: nothing to draw
+    const float lsep = s_lsep, lseq = s_lseq, it = a.inv_temperature;
+    const float *pr = a.c.ar_logits + ((int64_t)b * K + j) * V;
+    const float *qr = a.diff_logits + ((int64_t)b * K + j) * V;
+    const float *gr = a.gumbel + (int64_t)b * V;
+    const int begin = chunk * kSChunk, end = min(V, begin + kSChunk);
+    float bp = -INFINITY, ba = -INFINITY;   // best among p > q, best of log p + g
+    int ip = 0x7fffffff, ia = 0x7fffffff;
+    for (int i = begin + tid; i < end; i += 256) {
+        const float lp = pr[i] * it - lsep, lq = qr[i] * it - lseq;
+        const float g = gr[i];
+        const float r = expf(lp) - expf(lq);
+        if (r > 0.f) {
+            const float sc = logf(r) + g;
+            if (better_score(sc, i, bp, ip)) { bp = sc; ip = i; }
+        }
+        const float sa = lp + g;
+        if (better_score(sa, i, ba, ia)) { ba = sa; ia = i; }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float op = __shfl_xor(bp, off), oa = __shfl_xor(ba, off);
+        const int jp = __shfl_xor(ip, off), ja = __shfl_xor(ia, off);
+        if (better_score(op, jp, bp, ip)) { bp = op; ip = jp; }
+        if (better_score(oa, ja, ba, ia)) { ba = oa; ia = ja; }
+    }
+    __shared__ float4 sh[4];
+    if ((tid & 63) == 0) sh[tid >> 6] = make_float4(bp, __int_as_float(ip), ba, __int_as_float(ia));
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            if (better_score(sh[w].x, __float_as_int(sh[w].y), bp, ip)) { bp = sh[w].x; ip = __float_as_int(sh[w].y); }
+            if (better_score(sh[w].z, __float_as_int(sh[w].w), ba, ia)) { ba = sh[w].z; ia = __float_as_int(sh[w].w); }
+        }
+        a.draw_part[(int64_t)b * chunks + chunk] = make_float4(bp, __int_as_float(ip), ba, __int_as_float(ia));
+    }
+}
+
+// Same row copy as the greedy path.
+__device__ __forceinline__ void append_rows_s(const ConsensusArgs &a, int b, int layer, int L, int m, int tid, int nthreads)
+{
+    const int K = a.block_k, H = a.num_kv_heads, d = a.head_dim;
+    const int cpr = d / 8, per_tok = H * cpr, total = m * per_tok;
+    const int P = 1 << a.page_shift;
+    for (int e = tid; e < total; e += nthreads) {
+        const int k = e / per_tok, rem = e - k * per_tok;
+        const int g = rem / cpr, ch = rem - g * cpr;
+        const int pos = L + k;
+        const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + (pos >> a.page_shift)];
+        const int64_t src = ((((int64_t)layer * a.batch + b) * K + k) * H + g) * d + ch * 8;
+        const int64_t dst = (int64_t)layer * a.stride_layer + (int64_t)pg * a.stride_page +
+                            (int64_t)g * a.stride_head + (int64_t)(pos & (P - 1)) * a.stride_tok + ch * 8;
+        *(uint4 *)(a.k_pool + dst) = *(const uint4 *)(a.k_blk_ar + src);
+        *(uint4 *)(a.v_pool + dst) = *(const uint4 *)(a.v_blk_ar + src);
+    }
+}
+
+__global__ void __launch_bounds__(256) sample_commit_kernel(const SamplingArgs a)
+{
+    const ConsensusArgs &c = a.c;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int K = c.block_k, chunks = c.chunks;
+    __shared__ int s_L, s_m;
+    if (tid < 64) {
+        const int lane = tid;
+        float lp, lq;
+        const int j = first_rejected(a, b, lane, lp, lq);
+        int repl = -1;
+        if (j < K) {
+            float bp = -INFINITY, ba = -INFINITY;
+            int ip = 0x7fffffff, ia = 0x7fffffff;
+            for (int ch = 0; ch < chunks; ++ch) {  // every lane walks the chunks in order: same result in all lanes
+                const float4 t = a.draw_part[(int64_t)b * chunks + ch];
+                if (better_score(t.x, __float_as_int(t.y), bp, ip)) { bp = t.x; ip = __float_as_int(t.y); }
+                if (better_score(t.z, __float_as_int(t.w), ba, ia)) { ba = t.z; ia = __float_as_int(t.w); }
+            }
+            repl = ip != 0x7fffffff ? ip : ia;
+        }
+        const int m = min(j + 1, K);
+        if (lane < K) {
+            int t = -1;
+            if (lane < j) t = c.draft_tokens[(int64_t)b * K + lane];
+            else if (lane == j && lane < m) t = repl;
+            c.out_tokens[(int64_t)b * K + lane] = lane < m ? t : -1;
+        }
+        const int last_tok = (j < K) ? repl : c.draft_tokens[(int64_t)b * K + K - 1];
+        int committed = m, L = 0;
+        if (c.do_commit) {
+            L = c.seq_lens[b];
+            bool bad = false;
+            if (lane < m) {
+                const int pos = L + lane, slot = pos >> c.page_shift;
+                if (L < 0 || slot >= c.max_pages_per_seq) bad = true;
+                else {
+                    const int pg = c.page_table[(int64_t)b * c.max_pages_per_seq + slot];
+                    bad = pg < 0 || pg >= c.num_pages;
+                }
+            }
+            const bool any_bad = __ballot(bad) != 0ull;
+            if (any_bad) committed = 0;
+            if (lane == 0) {
+                c.commit_info[b * 2] = L;
+                c.commit_info[b * 2 + 1] = committed;
+                if (any_bad) atomicExch(c.err_word, -4);
+                else c.seq_lens[b] = L + m;
+            }
+        }
+        if (lane == 0) {
+            c.accept_len[b] = j;
+            c.num_committed[b] = committed;
+            c.next_anchor[b] = last_tok;
+            s_L = L;
+            s_m = c.do_commit ? committed : 0;
+        }
+    }
+    __syncthreads();
+    if (c.do_commit && c.num_layers <= kSInlineLayers && s_m > 0)
+        for (int layer = 0; layer < c.num_layers; ++layer) append_rows_s(c, b, layer, s_L, s_m, tid, 256);
+}
+
+__global__ void __launch_bounds__(256) sample_commit_layers_kernel(const SamplingArgs a)
+{
+    const int b = blockIdx.x, layer = blockIdx.y;
+    const int L = a.c.commit_info[b * 2], m = a.c.commit_info[b * 2 + 1];
+    if (m > 0) append_rows_s(a.c, b, layer, L, m, threadIdx.x, 256);
+}
+
+hipError_t launch_sampling_consensus(const SamplingArgs &a, hipStream_t stream)
+{
+    const ConsensusArgs &c = a.c;
+    if (c.batch == 0) return hipSuccess;
+    hipLaunchKernelGGL(lse_partial_kernel, dim3((unsigned)c.chunks * (unsigned)(c.batch * c.block_k)), dim3(256), 0,
+                       stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(draw_partial_kernel, dim3(c.chunks, c.batch), dim3(256), 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(sample_commit_kernel, dim3(c.batch), dim3(256), 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (c.do_commit && c.num_layers > kSInlineLayers) {
+        hipLaunchKernelGGL(sample_commit_layers_kernel, dim3(c.batch, c.num_layers), dim3(256), 0, stream, a);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+}  // namespace orthrus

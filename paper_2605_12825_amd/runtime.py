@@ -55,7 +55,7 @@ class DecodeStep:
         self.attn_ws = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
         self.cons_ws = None
         if vocab > 0:
-            n = B.orthrus_consensus_workspace_bytes(self.params)
+            n = max(B.orthrus_consensus_workspace_bytes(self.params), B.orthrus_sampling_workspace_bytes(self.params))
             self.cons_ws = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
 
     def set_max_seq_len(self, bound: int) -> None:
@@ -88,6 +88,14 @@ class DecodeStep:
         return B.orthrus_consensus_commit(self.ctx, self.params, ar_logits, draft_tokens, k_blk_ar, v_blk_ar,
                                           k_pool, v_pool, page_table, seq_lens, accept_len, num_committed,
                                           out_tokens, next_anchor, self.cons_ws, stream)
+
+    def sampling_consensus_commit(self, temperature, ar_logits, diff_logits, draft_tokens, accept_u, gumbel,
+                                  k_blk_ar, v_blk_ar, k_pool, v_pool, page_table, seq_lens, accept_len,
+                                  num_committed, out_tokens, next_anchor, stream=None):
+        return B.orthrus_sampling_consensus_commit(self.ctx, self.params, temperature, ar_logits, diff_logits,
+                                                   draft_tokens, accept_u, gumbel, k_blk_ar, v_blk_ar, k_pool, v_pool,
+                                                   page_table, seq_lens, accept_len, num_committed, out_tokens,
+                                                   next_anchor, self.cons_ws, stream)
 
     def device_error(self, stream=None) -> int:
         return B.orthrus_last_device_error(self.ctx, stream)
