@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="long")
     ap.add_argument("--num-splits", type=int, default=-1, help="-1: the workload's setting; 0: library chooses")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="0: greedy consensus (Eq. 8); > 0: lossless sampling consensus at that temperature")
     ap.add_argument("--paging", default="", help="override the workload's page-table layout: contiguous|shuffled|scattered")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-every", type=int, default=4,
@@ -71,7 +73,11 @@ def cpu_baseline(w, cache, host_sets, cons_sets):
         oracle.dual_view_attn(oracle.VIEW_AR_VERIFY, w.sm_scale, a["q"], a["k_blk"], a["v_blk"], *pools)
         if cons_sets:
             cs = cons_sets[rep % len(cons_sets)]
-            oracle.consensus_commit(cs["ar_logits"], cs["draft_tokens"])
+            if "diff_logits" in cs:
+                oracle.sampling_consensus_commit(cs["ar_logits"], cs["diff_logits"], cs["draft_tokens"],
+                                                 cs["accept_u"], cs["gumbel"], cs["temperature"])
+            else:
+                oracle.consensus_commit(cs["ar_logits"], cs["draft_tokens"])
         times.append(time.perf_counter() - t0)
         log("oracle step %d: %.2f s" % (rep, times[-1]))
         if time.perf_counter() - t_all > 10.0:
@@ -102,7 +108,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 5}))
         return
-    from orthrus_inputs import WORKLOADS, make_block, make_cache, make_consensus_case
+    from orthrus_inputs import WORKLOADS, make_block, make_cache, make_consensus_case, make_sampling_case
     from paper_2605_12825_amd import runtime as rt
 
     total_steps = args.warmup + args.steps
@@ -118,7 +124,13 @@ def main():
     for i in range(N_SETS):
         base = w.seed * 1000 + 10 * i
         host_sets.append((make_block(w, base + 1), make_block(w, base + 2)))
-    cons_sets = [make_consensus_case(w, w.seed * 1000 + 10 * i + 3) for i in range(N_SETS)] if w.vocab else []
+    T = args.temperature
+    if not w.vocab:
+        cons_sets = []
+    elif T > 0:
+        cons_sets = [make_sampling_case(w, w.seed * 1000 + 10 * i + 3, temperature=T) for i in range(N_SETS)]
+    else:
+        cons_sets = [make_consensus_case(w, w.seed * 1000 + 10 * i + 3) for i in range(N_SETS)]
     log("generated %s inputs in %.1f s" % (w.name, time.perf_counter() - t_gen))
 
     dev = torch.device("cuda:0")
@@ -126,7 +138,8 @@ def main():
     k_pool, v_pool = D(cache["k_pool"]), D(cache["v_pool"])
     page_table, seq_lens = D(cache["page_table"]), D(cache["seq_lens"])
     sets = [tuple({k: D(v) for k, v in blk.items()} for blk in pair) for pair in host_sets]
-    csets = [(D(c["ar_logits"]), D(c["draft_tokens"])) for c in cons_sets]
+    csets = [{k: D(v) for k, v in c.items() if isinstance(v, np.ndarray) and not k.startswith("planted")}
+             for c in cons_sets]
     B, K = w.batch, w.block_k
     o_d = torch.empty((B, K, w.num_q_heads, w.head_dim), dtype=torch.int16, device=dev)
     o_a = torch.empty_like(o_d)
@@ -157,9 +170,14 @@ def main():
         if record:
             ev[2].record(stream)
         if w.vocab:
-            lg, dr = csets[i % N_SETS]
-            step.consensus_commit(lg, dr, a["k_blk"], a["v_blk"], k_pool, v_pool, page_table, seq_lens, acc, ncm,
-                                  toks, anc)
+            cs = csets[i % N_SETS]
+            if T > 0:
+                step.sampling_consensus_commit(T, cs["ar_logits"], cs["diff_logits"], cs["draft_tokens"],
+                                               cs["accept_u"], cs["gumbel"], a["k_blk"], a["v_blk"], k_pool, v_pool,
+                                               page_table, seq_lens, acc, ncm, toks, anc)
+            else:
+                step.consensus_commit(cs["ar_logits"], cs["draft_tokens"], a["k_blk"], a["v_blk"], k_pool, v_pool,
+                                      page_table, seq_lens, acc, ncm, toks, anc)
             if record:
                 ev[3].record(stream)
         if record:
@@ -207,7 +225,8 @@ def main():
         if w.vocab:
             c_ms = np.array([ev[2].elapsed_time(ev[3]) for ev in call_events])
             extra["consensus_commit_us"] = round(float(c_ms.mean()) * 1e3, 2)
-            extra["consensus_logits_gbs"] = round(B * K * w.vocab * 4 / (float(c_ms.mean()) * 1e-3) / 1e9, 1)
+            nlog = 2 if T > 0 else 1
+            extra["consensus_logits_gbs"] = round(nlog * B * K * w.vocab * 4 / (float(c_ms.mean()) * 1e-3) / 1e9, 1)
     extra["kv_read_tbs_whole_step"] = round(2 * kv_bytes / (ms_per_step * 1e-3) / 1e12, 3)
     extra["tokens_committed_per_step"] = round(float((lens_after - lens_before).sum()) / args.steps / max(B, 1), 3)
 
@@ -219,8 +238,10 @@ def main():
         "config": {"workload": w.name, "description": w.description, "batch": B, "num_q_heads": w.num_q_heads,
                    "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim, "block_k": K,
                    "context": int(lens_before.max()), "page_size": w.page_size, "vocab": w.vocab,
-                   "num_splits": step.num_splits, "layers": 1,
-                   "step": "diffusion attn + AR verify attn" + (" + consensus + commit" if w.vocab else "")},
+                   "num_splits": step.num_splits, "layers": 1, "temperature": T,
+                   "step": "diffusion attn + AR verify attn" +
+                           ((" + sampling consensus + commit" if T > 0 else " + greedy consensus + commit")
+                            if w.vocab else "")},
         "roofline": roofline,
         "detail": extra,
     }
