@@ -54,6 +54,12 @@ def _load() -> ctypes.CDLL:
     if not os.path.exists(_build.LIB):
         # nothing built yet: build once; a stale library is the caller's to rebuild
         _build.build_library()
+    # PyTorch ships its own HIP runtime; load it first so that this library binds to that one.  Two
+    # HIP runtimes in one process do not share the GPU: whichever initialises second sees no device.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_build.LIB)
     vp, i32p = ctypes.c_void_p, ctypes.c_void_p
     pp = ctypes.POINTER(orthrus_params)

@@ -107,23 +107,32 @@ struct AttnGeom {
     static constexpr int DBLK = D / 32;       // 32-wide output blocks along d
 };
 
-// D head_dim, W waves (= 32-row blocks) per workgroup, NS LDS stages.
-template <int D, int W, int NS>
-__global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
+// D head_dim, W compute waves (= 32-row blocks) per workgroup, NS LDS stages.
+// LOADER: the workgroup has one more wave that issues every tile load and does nothing else.  A wave
+// that issues global->LDS loads is held up while the memory pipeline takes them (streaming 2 MB per CU
+// costs the issuing waves about as long as the arithmetic on it does), so when the compute waves issue
+// their own loads the two costs add up; with a dedicated loader wave they overlap.  Used whenever
+// W + 1 waves leave room for at least one workgroup per CU at two waves per SIMD (W <= 4).
+template <int D, int W, int NS, bool LOADER>
+__global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_kernel(const AttnArgs a)
 {
     using Gm = AttnGeom<D>;
     constexpr int CH = Gm::CH, ROWB = Gm::ROWB, RPI = Gm::RPI, NI = Gm::NI, GS = Gm::GS;
     constexpr int TILE_B = Gm::TILE_B, STAGE_B = Gm::STAGE_B, KSTEPS = Gm::KSTEPS, DBLK = Gm::DBLK;
-    constexpr int LPT = 2 * NI;        // load instructions per tile (K groups then V groups)
-    constexpr int MY = LPT / W;        // of which this wave issues MY
-    static_assert(LPT % W == 0, "waves must split a tile's loads evenly");
+    constexpr int LPT = 2 * NI;            // load instructions per tile (K groups then V groups)
+    constexpr int IW = LOADER ? 1 : W;     // waves that issue them
+    constexpr int MY = LPT / IW;           // loads per tile per issuing wave
+    static_assert(LPT % IW == 0, "issuing waves must split a tile's loads evenly");
     static_assert(NS >= 2 && NS <= 4, "stage count");
+    static_assert((NS - 2) * MY < 64, "outstanding loads must fit the vmcnt field");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = LOADER && wave == W;
+    const int iw = LOADER ? 0 : wave;      // index among the issuing waves
     const int col = lane & 31, h = lane >> 5;
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int K = a.block_k, G = a.group;
@@ -152,17 +161,21 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
     // through inline assembly so that whole tiles can stay in flight while older ones are computed;
     // completion is awaited explicitly with s_waitcnt vmcnt (loads return in order).  M0 carries the
     // LDS destination; nothing else in this kernel reads M0, and the compiler rewrites M0 itself
-    // right before any instruction of its own that needs it.
+    // right before any instruction of its own that needs it.  Two address forms: a 64-bit address per
+    // lane, or a wave-uniform 64-bit base plus a 32-bit byte offset per lane.
     auto dma16 = [&](const uint16_t *gp, uint32_t lds_addr) __attribute__((always_inline)) {
         asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                      :
                      : "v"(gp), "s"(lds_addr)
                      : "memory");
     };
+    auto dma16s = [&](const uint16_t *base, uint32_t voff, uint32_t lds_addr) __attribute__((always_inline)) {
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(voff), "s"(base), "s"(lds_addr)
+                     : "memory");
+    };
 
-    // Start this wave's share of the loads of tile t (cache tile, or the in-block tile when
-    // t == n_cache) into ring stage t % NS.  Rows past the end repeat the last valid row (finite data,
-    // masked later): nothing is fetched through an unmapped page and no LDS row is left undefined.
     // Page ids of the two 16-token halves of cache tile t (the second repeats the first when that
     // half lies past the end).  They are fetched one tile ahead of their use, so that the scalar
     // load's latency is never in front of a tile's loads.
@@ -176,6 +189,14 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
             if (ts + 16 < t_end) p1 = pt_row[(ts + 16) >> a.page_shift];
         }
     };
+    // Start this wave's share of the loads of tile t (cache tile, or the in-block tile when
+    // t == n_cache) into ring stage t % NS.  A full cache tile takes the cheap address form: page, head
+    // and row group go into a wave-uniform base (scalar arithmetic), the lane adds one loop-invariant
+    // byte offset.  In the last, ragged cache tile rows past the end repeat the last valid row (finite
+    // data, masked later): nothing is fetched through an unmapped page and no LDS row is left
+    // undefined; that tile and the in-block tile compute an address per lane.
+    const uint32_t lane_off = (uint32_t)(ld_tok * (int)a.stride_tok + ((ld_ch ^ xm<CH>(ld_tok)) << 3)) * 2u;
+    const int64_t head_off = (int64_t)g * a.stride_head;
     auto issue_tile = [&](int t, int p0, int p1) __attribute__((always_inline)) {
         const uint32_t dst = smem_lds + (t % NS) * STAGE_B;
         if (t < n_cache) {
@@ -185,22 +206,35 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
                 if (p0 < 0 || p0 >= a.num_pages) p0 = 0;
                 if (p1 < 0 || p1 >= a.num_pages) p1 = 0;
             }
+            if (ts + 32 <= t_end) {
+                const int tsp = ts & (P - 1);
 #pragma unroll
-            for (int e = 0; e < MY; ++e) {
-                const int id = wave + e * W;              // 0..LPT-1: K groups, then V groups
-                const int u = id % NI;
-                const uint16_t *pool = id < NI ? a.k_pool : a.v_pool;
-                const int tok = u * RPI + ld_tok;
-                const int tg = min(ts + tok, t_end - 1);
-                const int p = (u * RPI < 16) ? p0 : p1;
-                const int64_t off = (int64_t)p * a.stride_page + (int64_t)g * a.stride_head +
-                                    (int64_t)(tg & (P - 1)) * a.stride_tok + ((ld_ch ^ xm<CH>(ld_tok)) << 3);
-                dma16(pool + off, dst + (id < NI ? 0 : TILE_B) + u * GS);
+                for (int e = 0; e < MY; ++e) {
+                    const int id = iw + e * IW;               // 0..LPT-1: K groups, then V groups
+                    const int u = id % NI;
+                    const int page = (u * RPI < 16) ? p0 : p1;
+                    const int tin = (tsp + u * RPI) & (P - 1);
+                    const int64_t soff = (int64_t)page * a.stride_page + head_off + (int64_t)tin * a.stride_tok;
+                    dma16s((id < NI ? a.k_pool : a.v_pool) + soff, lane_off, dst + (id < NI ? 0 : TILE_B) + u * GS);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < MY; ++e) {
+                    const int id = iw + e * IW;
+                    const int u = id % NI;
+                    const uint16_t *pool = id < NI ? a.k_pool : a.v_pool;
+                    const int tok = u * RPI + ld_tok;
+                    const int tg = min(ts + tok, t_end - 1);
+                    const int p = (u * RPI < 16) ? p0 : p1;
+                    const int64_t off = (int64_t)p * a.stride_page + (int64_t)g * a.stride_head +
+                                        (int64_t)(tg & (P - 1)) * a.stride_tok + ((ld_ch ^ xm<CH>(ld_tok)) << 3);
+                    dma16(pool + off, dst + (id < NI ? 0 : TILE_B) + u * GS);
+                }
             }
         } else {
 #pragma unroll
             for (int e = 0; e < MY; ++e) {
-                const int id = wave + e * W;
+                const int id = iw + e * IW;
                 const int u = id % NI;
                 const uint16_t *blk = id < NI ? a.k_blk : a.v_blk;
                 const int tok = u * RPI + ld_tok;
@@ -211,16 +245,39 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
         }
     };
 
-    // ---- prologue: fill the ring, then fetch the queries while those loads are in flight
-    int np0, np1;  // page ids of the next tile to be issued
+    // One step of the load pipeline, run by every issuing wave once per tile i, around the tile's
+    // workgroup barrier: before the barrier this wave's loads of tile i are complete; after it, so are
+    // everybody's, and every wave is done reading stage (i-1) % NS, which is refilled with tile
+    // i+NS-1 while tile i is computed.
+    int np0 = 0, np1 = 0;  // page ids of the next tile to be issued
+    auto pipeline_fill = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int t = 0; t < NS - 1; ++t) {
-        fetch_pages(t, np0, np1);
-        if (t < n_tiles) issue_tile(t, np0, np1);
+        for (int t = 0; t < NS - 1; ++t) {
+            fetch_pages(t, np0, np1);
+            if (t < n_tiles) issue_tile(t, np0, np1);
+        }
+        fetch_pages(NS - 1, np0, np1);
+    };
+    auto pipeline_step = [&](int i) __attribute__((always_inline)) {
+        const int ahead = min(NS - 2, n_tiles - 1 - i);  // tiles issued after tile i so far
+        if (ahead >= 2) wait_vmcnt<2 * MY>();
+        else if (ahead == 1) wait_vmcnt<MY>();
+        else wait_vmcnt<0>();
+        wg_barrier();
+        if (i + NS - 1 < n_tiles) issue_tile(i + NS - 1, np0, np1);
+        fetch_pages(i + NS, np0, np1);
+    };
+
+    if (loader) {
+        // the loader wave: nothing but the load pipeline; its last wait leaves no load outstanding
+        pipeline_fill();
+        for (int i = 0; i < n_tiles; ++i) pipeline_step(i);
+        return;
     }
-    fetch_pages(NS - 1, np0, np1);
+    if (!LOADER) pipeline_fill();
 
     // queries: B operand of S^T = K.Q^T, lane holds row `col` of this wave's block, d = 16*kk + 8*h .. +7
+    // (fetched while the first tiles are in flight)
     Frag qf[KSTEPS];
     int irow;
     const int ridx = wave * 32 + col;
@@ -267,18 +324,11 @@ __global__ void __launch_bounds__(64 * W, 2) attn_split_kernel(const AttnArgs a)
                      ((lane & 1) << 3);
     }
 
-    // ---- main loop: one barrier per tile.  Before it, this wave's loads of tile i are complete; after
-    //      it, so are everybody's, and everybody is done reading stage (i-1) % NS, which is refilled
-    //      with tile i+NS-1 while tile i is computed.
+    // ---- main loop: one barrier per tile
     int stage = 0;  // ring slot of tile i (= i % NS)
     for (int i = 0; i < n_tiles; ++i) {
-        const int ahead = min(NS - 2, n_tiles - 1 - i);  // tiles issued after tile i so far
-        if (ahead >= 2) wait_vmcnt<2 * MY>();
-        else if (ahead == 1) wait_vmcnt<MY>();
-        else wait_vmcnt<0>();
-        wg_barrier();
-        if (i + NS - 1 < n_tiles) issue_tile(i + NS - 1, np0, np1);
-        fetch_pages(i + NS, np0, np1);
+        if (LOADER) wg_barrier();
+        else pipeline_step(i);
 
         // LDS addresses of this tile's operands: one add per base, the rest are instruction offsets
         const uint32_t st_addr = smem_lds + (uint32_t)stage * STAGE_B;
@@ -471,6 +521,10 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
 #define ORTHRUS_ATTN_STAGES 3
 #endif
 constexpr int kStages = ORTHRUS_ATTN_STAGES;  // LDS ring depth (2..4)
+#ifndef ORTHRUS_ATTN_LOADER_MAX_W
+#define ORTHRUS_ATTN_LOADER_MAX_W 4
+#endif
+constexpr int kMaxLoaderWaves = ORTHRUS_ATTN_LOADER_MAX_W;  // workgroups of up to this many compute waves get a loader wave
 
 static size_t lds_need(int head_dim)
 {
@@ -489,8 +543,9 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     plan->lds_bytes = lds_need(head_dim);
     const int64_t units = (int64_t)batch * num_kv_heads;
     // workgroups resident per CU: LDS ring size and 8 waves (2 per SIMD at <= 256 registers)
+    const int wg_waves = W + (W <= kMaxLoaderWaves ? 1 : 0);
     int per_cu = (int)(160 * 1024 / plan->lds_bytes);
-    if (per_cu > 8 / W) per_cu = 8 / W;
+    if (per_cu > 8 / wg_waves) per_cu = 8 / wg_waves;
     if (per_cu < 1) per_cu = 1;
     int splits;
     if (requested_splits > 0) {
@@ -498,8 +553,9 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     } else {
         // Pick the split count with a small cost model (times in microseconds), using max_seq_len for
         // every sequence: workgroups run in rounds of `slots`; a round streams at the practical HBM
-        // rate once every CU holds at least 4 streaming waves; every split beyond the first writes and
-        // re-reads an fp32 partial (rows x d x 4 bytes) and adds the combine launch.
+        // rate once every CU holds a workgroup with a loader wave (or, without one, at least 4 waves
+        // that stream and compute in turns); every split beyond the first writes and re-reads an fp32
+        // partial (rows x d x 4 bytes) and adds the combine launch.
         const double kRate = 6.0e6;          // bytes per microsecond (practical streaming ceiling)
         const double kRound = 5.0, kCombine = 8.0;
         const int64_t slots = (int64_t)num_cus * per_cu;
@@ -514,10 +570,9 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
             double t = s > 1 ? kCombine : 0.0;
             for (int64_t left = wgs; left > 0; left -= slots) {
                 const int64_t now = left < slots ? left : slots;
-                // workgroups spread over the CUs first; a CU streams at its share of the HBM rate once
-                // it holds at least 4 waves
+                // workgroups spread over the CUs first; a CU that streams gets its share of the HBM rate
                 const double active = now < num_cus ? (double)now : (double)num_cus;
-                double per_cu_waves = (double)now * W / active / 4.0;
+                double per_cu_waves = W <= kMaxLoaderWaves ? 1.0 : (double)now * W / active / 4.0;
                 if (per_cu_waves > 1.0) per_cu_waves = 1.0;
                 const double f = active / num_cus * per_cu_waves;
                 t += kRound + per_wg * now / (kRate * f);
@@ -544,9 +599,10 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
 template <int D, int W>
 static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStream_t stream)
 {
-    auto kern = attn_split_kernel<D, W, kStages>;
+    constexpr bool kLoader = W <= kMaxLoaderWaves;
+    auto kern = attn_split_kernel<D, W, kStages, kLoader>;
     dim3 grid(plan.num_splits, a.num_kv_heads, a.batch);
-    hipLaunchKernelGGL(kern, grid, dim3(64 * W), plan.lds_bytes, stream, a);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * (W + (kLoader ? 1 : 0))), plan.lds_bytes, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (plan.num_splits > 1) {
