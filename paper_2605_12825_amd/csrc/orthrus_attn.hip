@@ -522,7 +522,7 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
 #endif
 constexpr int kStages = ORTHRUS_ATTN_STAGES;  // LDS ring depth (2..4)
 #ifndef ORTHRUS_ATTN_LOADER_MAX_W
-#define ORTHRUS_ATTN_LOADER_MAX_W 4
+#define ORTHRUS_ATTN_LOADER_MAX_W 8
 #endif
 constexpr int kMaxLoaderWaves = ORTHRUS_ATTN_LOADER_MAX_W;  // workgroups of up to this many compute waves get a loader wave
 
@@ -542,10 +542,12 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     plan->rows_padded = W * 32;
     plan->lds_bytes = lds_need(head_dim);
     const int64_t units = (int64_t)batch * num_kv_heads;
-    // workgroups resident per CU: LDS ring size and 8 waves (2 per SIMD at <= 256 registers)
-    const int wg_waves = W + (W <= kMaxLoaderWaves ? 1 : 0);
+    // workgroups resident per CU: LDS ring size, and 12 waves with a loader wave (3 per SIMD: the
+    // compute waves stay below 168 registers) or 8 waves without (2 per SIMD at <= 256 registers)
+    const bool has_loader = W <= kMaxLoaderWaves;
+    const int wg_waves = W + (has_loader ? 1 : 0), cu_waves = has_loader ? 12 : 8;
     int per_cu = (int)(160 * 1024 / plan->lds_bytes);
-    if (per_cu > 8 / wg_waves) per_cu = 8 / wg_waves;
+    if (per_cu > cu_waves / wg_waves) per_cu = cu_waves / wg_waves;
     if (per_cu < 1) per_cu = 1;
     int splits;
     if (requested_splits > 0) {
