@@ -25,11 +25,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E published peak
 N_SETS = 4              # rotating sets of block inputs / logits (fresh data every step, cycled)
-# HBM bytes per orthrus_dual_view_attn call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# HBM bytes per attn_split_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (counters scaled by what they read for a plain 1 GiB copy; see profiles/), keyed by
-# (workload, splits).  Reads + writes of the split kernel and the combine kernel.
-MEASURED_TRAFFIC_BYTES = {("long", 16): int((542.22 + 17.87 + 17.04 + 0.52) * 1e6),
-                          ("stress", 1): int((558.66 + 8.39) * 1e6)}
+# (workload, splits): reads + writes of that kernel.
+MEASURED_TRAFFIC_BYTES = {("long", 8): int((542.28 + 8.52) * 1e6),
+                          ("stress", 1): int((558.74 + 8.39) * 1e6)}
 
 
 def log(*a):
@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--paging", default="", help="override the workload's page-table layout: contiguous|shuffled|scattered")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-every", type=int, default=4,
-                    help="bracket the library calls of every Nth timed step with HIP events (0: never)")
+                    help="time the kernels of every Nth timed step with HIP events (0: never)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (known traffic, used to "
                          "scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -159,17 +159,19 @@ def main():
         # (no device round trip); it sizes the attention grid of this step
         step.set_max_seq_len(min(cap, len0 + (i if w.vocab else 0) * K))
         d, a = sets[i % N_SETS]
-        ev = None
-        if record:
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4 if w.vocab else 3)]
-            ev[0].record(stream)
+        # sampled steps: the library attaches HIP events to its attention kernels' own dispatches
+        # (kernel execution time, no marker between kernels); the consensus call sits between two
+        # ordinary events on the same stream
+        step.attn_timing(record)
         step.attn(0, d["q"], d["k_blk"], d["v_blk"], k_pool, v_pool, page_table, seq_lens, o_d)
-        if record:
-            ev[1].record(stream)
         step.attn(1, a["q"], a["k_blk"], a["v_blk"], k_pool, v_pool, page_table, seq_lens, o_a)
         if record:
-            ev[2].record(stream)
+            step.attn_timing(False)
         if w.vocab:
+            ev = None
+            if record:
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                ev[0].record(stream)
             cs = csets[i % N_SETS]
             if T > 0:
                 step.sampling_consensus_commit(T, cs["ar_logits"], cs["diff_logits"], cs["draft_tokens"],
@@ -179,9 +181,8 @@ def main():
                 step.consensus_commit(cs["ar_logits"], cs["draft_tokens"], a["k_blk"], a["v_blk"], k_pool, v_pool,
                                       page_table, seq_lens, acc, ncm, toks, anc)
             if record:
-                ev[3].record(stream)
-        if record:
-            call_events.append(ev)
+                ev[1].record(stream)
+                call_events.append(ev)
 
     for i in range(args.warmup):
         run_step(i, False)
@@ -208,25 +209,29 @@ def main():
     kv_bytes = mean_tokens * w.num_kv_heads * 2 * w.head_dim * 2
     roofline = None
     extra = {}
-    if call_events:
-        d_ms = np.array([ev[0].elapsed_time(ev[1]) for ev in call_events])
-        a_ms = np.array([ev[1].elapsed_time(ev[2]) for ev in call_events])
-        attn_ms = float(np.concatenate([d_ms, a_ms]).mean())
-        achieved = kv_bytes / (attn_ms * 1e-3) / 1e9
+    split_us, split_n, comb_us, comb_n = step.attn_timing_read()
+    if split_n:
+        split_avg = split_us / split_n
+        comb_avg = comb_us / comb_n if comb_n else 0.0
+        achieved = kv_bytes / (split_avg * 1e-6) / 1e9
+        call_gbs = kv_bytes / ((split_avg + comb_avg) * 1e-6) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4),
                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, step.num_splits)),
-                    "kernel": "orthrus_dual_view_attn = attn_split_kernel" +
-                              (" + attn_combine_kernel" if step.num_splits > 1 else ""),
-                    "events": "HIP events around every %d-th call pair inside the timed region" % args.event_every,
-                    "avg_launch_us": round(attn_ms * 1e3, 2), "algorithmic_bytes_per_launch": int(kv_bytes)}
-        extra["diffusion_attn_us"] = round(float(d_ms.mean()) * 1e3, 2)
-        extra["verify_attn_us"] = round(float(a_ms.mean()) * 1e3, 2)
-        if w.vocab:
-            c_ms = np.array([ev[2].elapsed_time(ev[3]) for ev in call_events])
-            extra["consensus_commit_us"] = round(float(c_ms.mean()) * 1e3, 2)
-            nlog = 2 if T > 0 else 1
-            extra["consensus_logits_gbs"] = round(nlog * B * K * w.vocab * 4 / (float(c_ms.mean()) * 1e-3) / 1e9, 1)
+                    "kernel": "attn_split_kernel",
+                    "events": "HIP events attached to the kernel's own dispatches in every %d-th timed step "
+                              "(%d launches)" % (args.event_every, split_n),
+                    "avg_launch_us": round(split_avg, 2), "algorithmic_bytes_per_launch": int(kv_bytes)}
+        extra["attn_split_kernel_us"] = round(split_avg, 2)
+        extra["attn_combine_kernel_us"] = round(comb_avg, 2)
+        extra["attn_call_kernels_us"] = round(split_avg + comb_avg, 2)
+        extra["attn_call_kv_gbs"] = round(call_gbs, 1)
+        extra["attn_call_frac_of_peak"] = round(call_gbs / HBM_PEAK_GBS, 4)
+    if call_events:
+        c_ms = np.array([ev[0].elapsed_time(ev[1]) for ev in call_events])
+        extra["consensus_commit_us"] = round(float(c_ms.mean()) * 1e3, 2)
+        nlog = 2 if T > 0 else 1
+        extra["consensus_logits_gbs"] = round(nlog * B * K * w.vocab * 4 / (float(c_ms.mean()) * 1e-3) / 1e9, 1)
     extra["kv_read_tbs_whole_step"] = round(2 * kv_bytes / (ms_per_step * 1e-3) / 1e12, 3)
     extra["tokens_committed_per_step"] = round(float((lens_after - lens_before).sum()) / args.steps / max(B, 1), 3)
 

@@ -205,6 +205,21 @@ orthrus_status orthrus_sampling_consensus_commit(orthrus_ctx *ctx, const orthrus
                                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Per-kernel timing of orthrus_dual_view_attn, for measurement (Section 4 reports throughput; this is
+ * how this library's own kernels are timed).  While enabled (enable != 0), every attention call made
+ * with `ctx` attaches a pair of HIP events to each kernel it launches (the split kernel and, when the
+ * plan has more than one split, the combine kernel): the events belong to the dispatches themselves, so
+ * the elapsed time between them is the kernel's execution time and nothing is inserted between
+ * kernels.  Events are created on first use and recycled (host-side allocation only; do not enable
+ * under stream capture).  orthrus_attn_timing_read waits for the recorded kernels to finish, returns
+ * the sums of kernel times in microseconds and the launch counts accumulated since the last read
+ * (all [host] pointers), and resets them.
+ */
+orthrus_status orthrus_attn_timing(orthrus_ctx *ctx, int enable);
+orthrus_status orthrus_attn_timing_read(orthrus_ctx *ctx, double *split_us, int64_t *split_launches,
+                                        double *combine_us, int64_t *combine_launches);
+
+/*
  * Synchronises `stream`, copies the context's device error word to *code [host] (ORTHRUS_OK or
  * ORTHRUS_ECAPACITY) and clears it.  This is the only entry point that blocks.
  */

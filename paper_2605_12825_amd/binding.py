@@ -27,7 +27,7 @@ EXPORTED = [
     "orthrus_create", "orthrus_destroy", "orthrus_status_string", "orthrus_attn_workspace_bytes",
     "orthrus_consensus_workspace_bytes", "orthrus_sampling_workspace_bytes", "orthrus_attn_num_splits",
     "orthrus_dual_view_attn", "orthrus_consensus_commit", "orthrus_sampling_consensus_commit",
-    "orthrus_last_device_error",
+    "orthrus_attn_timing", "orthrus_attn_timing_read", "orthrus_last_device_error",
 ]
 
 
@@ -86,6 +86,11 @@ def _load() -> ctypes.CDLL:
     lib.orthrus_sampling_consensus_commit.restype = ctypes.c_int
     lib.orthrus_sampling_consensus_commit.argtypes = [vp, pp, ctypes.c_float, vp, vp, i32p, vp, vp, vp, vp, vp, vp,
                                                       i32p, i32p, i32p, i32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+    lib.orthrus_attn_timing.restype = ctypes.c_int
+    lib.orthrus_attn_timing.argtypes = [vp, ctypes.c_int]
+    lib.orthrus_attn_timing_read.restype = ctypes.c_int
+    lib.orthrus_attn_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
+                                             ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.orthrus_last_device_error.restype = ctypes.c_int
     lib.orthrus_last_device_error.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
     return lib
@@ -201,6 +206,22 @@ def orthrus_sampling_consensus_commit(ctx, p: orthrus_params, temperature: float
     if check and st != ORTHRUS_OK:
         raise OrthrusError(st, "orthrus_sampling_consensus_commit")
     return st
+
+
+def orthrus_attn_timing(ctx, enable: bool) -> None:
+    st = _lib.orthrus_attn_timing(ctx, 1 if enable else 0)
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_attn_timing")
+
+
+def orthrus_attn_timing_read(ctx):
+    """(split kernel microseconds, launches, combine kernel microseconds, launches) since the last read."""
+    su, cu = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    sn, cn = ctypes.c_int64(0), ctypes.c_int64(0)
+    st = _lib.orthrus_attn_timing_read(ctx, ctypes.byref(su), ctypes.byref(sn), ctypes.byref(cu), ctypes.byref(cn))
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_attn_timing_read")
+    return su.value, sn.value, cu.value, cn.value
 
 
 def orthrus_last_device_error(ctx, stream=None) -> int:

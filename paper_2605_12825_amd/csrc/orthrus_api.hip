@@ -6,11 +6,19 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <vector>
 
 struct orthrus_ctx {
     int device;
     int num_cus;
     int32_t *err_word;  // device
+    // optional per-kernel timing of the attention launches (orthrus_attn_timing*)
+    bool timing = false;
+    std::vector<hipEvent_t> free_events;
+    struct Pending { hipEvent_t start, stop; int kind; };
+    std::vector<Pending> pending;
+    double sum_us[2] = {0.0, 0.0};
+    int64_t launches[2] = {0, 0};
 };
 
 namespace {
@@ -119,6 +127,8 @@ orthrus_status orthrus_destroy(orthrus_ctx *ctx)
 {
     if (!ctx) return ORTHRUS_EINVAL;
     hipError_t e = hipFree(ctx->err_word);
+    for (auto &pd : ctx->pending) { hipEventDestroy(pd.start); hipEventDestroy(pd.stop); }
+    for (auto ev : ctx->free_events) hipEventDestroy(ev);
     delete ctx;
     return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
 }
@@ -192,8 +202,63 @@ orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p,
     a.max_seq_len = p->max_seq_len; a.chunk_tokens = plan.chunk_tokens; a.num_splits = plan.num_splits;
     a.view = (int)view;
     a.scale_log2e = p->sm_scale * 1.4426950408889634f;
-    hipError_t e = orthrus::launch_attn(a, plan, p->head_dim, (hipStream_t)stream);
+    orthrus::AttnLaunchEvents ev;
+    if (ctx->timing) {
+        ev.on = true;
+        for (int k = 0; k < 2; ++k) {
+            for (hipEvent_t *slot : {&ev.start[k], &ev.stop[k]}) {
+                if (!ctx->free_events.empty()) {
+                    *slot = ctx->free_events.back();
+                    ctx->free_events.pop_back();
+                } else if (hipEventCreate(slot) != hipSuccess) {
+                    return ORTHRUS_EHIP;
+                }
+            }
+        }
+    }
+    hipError_t e = orthrus::launch_attn(a, plan, p->head_dim, (hipStream_t)stream, &ev);
+    if (ev.on) {
+        for (int k = 0; k < 2; ++k) {
+            if (ev.used[k] && e == hipSuccess) {
+                ctx->pending.push_back({ev.start[k], ev.stop[k], k});
+            } else {
+                ctx->free_events.push_back(ev.start[k]);
+                ctx->free_events.push_back(ev.stop[k]);
+            }
+        }
+    }
     return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
+orthrus_status orthrus_attn_timing(orthrus_ctx *ctx, int enable)
+{
+    if (!ctx) return ORTHRUS_EINVAL;
+    ctx->timing = enable != 0;
+    return ORTHRUS_OK;
+}
+
+orthrus_status orthrus_attn_timing_read(orthrus_ctx *ctx, double *split_us, int64_t *split_launches,
+                                        double *combine_us, int64_t *combine_launches)
+{
+    if (!ctx || !split_us || !split_launches || !combine_us || !combine_launches) return ORTHRUS_EINVAL;
+    orthrus_status st = ORTHRUS_OK;
+    for (auto &pd : ctx->pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(pd.stop) != hipSuccess || hipEventElapsedTime(&ms, pd.start, pd.stop) != hipSuccess) {
+            st = ORTHRUS_EHIP;
+        } else {
+            ctx->sum_us[pd.kind] += (double)ms * 1000.0;
+            ctx->launches[pd.kind] += 1;
+        }
+        ctx->free_events.push_back(pd.start);
+        ctx->free_events.push_back(pd.stop);
+    }
+    ctx->pending.clear();
+    *split_us = ctx->sum_us[0]; *split_launches = ctx->launches[0];
+    *combine_us = ctx->sum_us[1]; *combine_launches = ctx->launches[1];
+    ctx->sum_us[0] = ctx->sum_us[1] = 0.0;
+    ctx->launches[0] = ctx->launches[1] = 0;
+    return st;
 }
 
 orthrus_status orthrus_consensus_commit(orthrus_ctx *ctx, const orthrus_params *p,

@@ -25,6 +25,8 @@
 //            attn_combine_kernel merges in a fixed split order (deterministic).
 #include "orthrus_internal.h"
 
+#include <hip/hip_ext.h>
+
 namespace orthrus {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -599,35 +601,49 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
 }
 
 template <int D, int W>
-static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStream_t stream)
+static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStream_t stream, AttnLaunchEvents *ev)
 {
     constexpr bool kLoader = W <= kMaxLoaderWaves;
     auto kern = attn_split_kernel<D, W, kStages, kLoader>;
+    const bool timed = ev && ev->on;
     dim3 grid(plan.num_splits, a.num_kv_heads, a.batch);
-    hipLaunchKernelGGL(kern, grid, dim3(64 * (W + (kLoader ? 1 : 0))), plan.lds_bytes, stream, a);
+    dim3 block(64 * (W + (kLoader ? 1 : 0)));
+    if (timed) {
+        hipExtLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, ev->start[0], ev->stop[0], 0, a);
+        ev->used[0] = true;
+    } else {
+        hipLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (plan.num_splits > 1) {
         dim3 cgrid((unsigned)(a.batch * a.num_kv_heads) * W * (D / 32));
-        hipLaunchKernelGGL((attn_combine_kernel<D, W>), cgrid, dim3(256), 0, stream, a);
+        if (timed) {
+            hipExtLaunchKernelGGL((attn_combine_kernel<D, W>), cgrid, dim3(256), 0, stream, ev->start[1], ev->stop[1],
+                                  0, a);
+            ev->used[1] = true;
+        } else {
+            hipLaunchKernelGGL((attn_combine_kernel<D, W>), cgrid, dim3(256), 0, stream, a);
+        }
         e = hipGetLastError();
     }
     return e;
 }
 
-hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream)
+hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream,
+                       AttnLaunchEvents *events)
 {
     if (a.batch == 0) return hipSuccess;
     const int key = head_dim * 10 + plan.waves;
     switch (key) {
-    case 1281: return launch_variant<128, 1>(a, plan, stream);
-    case 1282: return launch_variant<128, 2>(a, plan, stream);
-    case 1284: return launch_variant<128, 4>(a, plan, stream);
-    case 1288: return launch_variant<128, 8>(a, plan, stream);
-    case 641: return launch_variant<64, 1>(a, plan, stream);
-    case 642: return launch_variant<64, 2>(a, plan, stream);
-    case 644: return launch_variant<64, 4>(a, plan, stream);
-    case 648: return launch_variant<64, 8>(a, plan, stream);
+    case 1281: return launch_variant<128, 1>(a, plan, stream, events);
+    case 1282: return launch_variant<128, 2>(a, plan, stream, events);
+    case 1284: return launch_variant<128, 4>(a, plan, stream, events);
+    case 1288: return launch_variant<128, 8>(a, plan, stream, events);
+    case 641: return launch_variant<64, 1>(a, plan, stream, events);
+    case 642: return launch_variant<64, 2>(a, plan, stream, events);
+    case 644: return launch_variant<64, 4>(a, plan, stream, events);
+    case 648: return launch_variant<64, 8>(a, plan, stream, events);
     }
     return hipErrorInvalidValue;
 }

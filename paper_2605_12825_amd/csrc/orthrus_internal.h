@@ -58,10 +58,20 @@ struct SamplingArgs {
     float inv_temperature;
 };
 
+// Optional start/stop events of the two attention kernels of one call (index 0 = split kernel,
+// 1 = combine kernel).  When `on`, the launcher attaches them to the dispatches themselves, so that
+// hipEventElapsedTime(start, stop) is the kernel's own execution time without any marker in between.
+struct AttnLaunchEvents {
+    bool on = false;
+    hipEvent_t start[2] = {nullptr, nullptr}, stop[2] = {nullptr, nullptr};
+    bool used[2] = {false, false};
+};
+
 // Host-side launchers (defined next to the kernels).  Return hipSuccess or the launch error.
 hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv_heads, int max_seq_len,
                      int requested_splits, int num_cus, AttnPlan *plan);
-hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream);
+hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream,
+                       AttnLaunchEvents *events = nullptr);
 hipError_t launch_consensus(const ConsensusArgs &a, hipStream_t stream);
 hipError_t launch_sampling_consensus(const SamplingArgs &a, hipStream_t stream);
 int consensus_chunk_elems();

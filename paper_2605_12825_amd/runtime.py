@@ -97,5 +97,13 @@ class DecodeStep:
                                                    page_table, seq_lens, accept_len, num_committed, out_tokens,
                                                    next_anchor, self.cons_ws, stream)
 
+    def attn_timing(self, enable: bool) -> None:
+        """Attach HIP events to the attention kernels of the following attn() calls (or stop doing so)."""
+        B.orthrus_attn_timing(self.ctx, enable)
+
+    def attn_timing_read(self):
+        """(split us, launches, combine us, launches) summed over the timed launches since the last read."""
+        return B.orthrus_attn_timing_read(self.ctx)
+
     def device_error(self, stream=None) -> int:
         return B.orthrus_last_device_error(self.ctx, stream)

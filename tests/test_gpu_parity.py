@@ -85,6 +85,28 @@ def test_tiny_config_attention(view):
     np.testing.assert_allclose(lse, want_lse, rtol=0, atol=2e-3)
 
 
+def test_attention_kernel_timing_hooks():
+    """Timing attaches events to the launches and changes no result; counts follow the launch plan."""
+    w = Workload(name="tm", seed=77, batch=2, num_q_heads=8, num_kv_heads=2, head_dim=128, block_k=16,
+                 context_range=(300, 700), page_size=16, paging="shuffled")
+    cache = make_cache(w)
+    blk = make_block(w, 78)
+    for splits in (1, 3):
+        case = GpuCase(w, cache, num_splits=splits)
+        plain = case.attn(AR, blk, want_lse=False)
+        assert case.step.attn_timing_read() == (0.0, 0, 0.0, 0)
+        case.step.attn_timing(True)
+        timed = [case.attn(AR, blk, want_lse=False) for _ in range(3)]
+        case.step.attn_timing(False)
+        untimed = case.attn(AR, blk, want_lse=False)
+        split_us, split_n, comb_us, comb_n = case.step.attn_timing_read()
+        assert split_n == 3 and comb_n == (3 if splits > 1 else 0)
+        assert 0.0 < split_us < 3e4 and (comb_us > 0.0) == (splits > 1)
+        assert case.step.attn_timing_read() == (0.0, 0, 0.0, 0)
+        for t in timed + [untimed]:
+            np.testing.assert_array_equal(t, plain)
+
+
 SMALL = [
     # several tiles and ragged tails, every row-block variant, both head sizes, odd group sizes
     dict(batch=2, num_q_heads=4, num_kv_heads=2, head_dim=64, block_k=4, context_range=(0, 200), page_size=16),
