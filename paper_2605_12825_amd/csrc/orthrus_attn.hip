@@ -3,7 +3,7 @@
 // the block, AR verification view causal inside the block).
 //
 // Work decomposition
-//   grid   = (split, KV head g, sequence b).  A workgroup streams cache tokens
+//   grid   = one workgroup per (split, KV head g, sequence b).  A workgroup streams cache tokens
 //            [split*chunk, min(L_b, (split+1)*chunk)) of KV head g once and serves all R = G*K
 //            query rows that share that KV head (G query heads x K block rows).
 //   waves  = W per workgroup, one per block of 32 query rows (W = 1, 2, 4 or 8).  Every wave reads
@@ -136,7 +136,13 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
     const bool loader = LOADER && wave == W;
     const int iw = LOADER ? 0 : wave;      // index among the issuing waves
     const int col = lane & 31, h = lane >> 5;
-    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    // Workgroup id -> (sequence, split, KV head) with the sequence index fastest and the head slowest.
+    // Consecutive workgroup ids go to different XCDs; a head's rows sit at a fixed offset inside every
+    // page, so an order that ties XCD k to head k makes each XCD hammer its own subset of the HBM
+    // channels and the XCDs finish far apart.
+    const int b = (int)(blockIdx.x % (unsigned)a.batch);
+    const int split = (int)((blockIdx.x / (unsigned)a.batch) % (unsigned)a.num_splits);
+    const int g = (int)(blockIdx.x / ((unsigned)a.batch * (unsigned)a.num_splits));
     const int K = a.block_k, G = a.group;
     const int P = 1 << a.page_shift;
 
@@ -606,7 +612,7 @@ static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStr
     constexpr bool kLoader = W <= kMaxLoaderWaves;
     auto kern = attn_split_kernel<D, W, kStages, kLoader>;
     const bool timed = ev && ev->on;
-    dim3 grid(plan.num_splits, a.num_kv_heads, a.batch);
+    dim3 grid((unsigned)plan.num_splits * (unsigned)a.num_kv_heads * (unsigned)a.batch);
     dim3 block(64 * (W + (kLoader ? 1 : 0)));
     if (timed) {
         hipExtLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, ev->start[0], ev->stop[0], 0, a);
