@@ -30,6 +30,7 @@ extern "C" {
 #endif
 
 typedef struct orthrus_ctx orthrus_ctx; /* opaque: device id, cached device properties, a device error word */
+typedef struct orthrus_graph orthrus_graph; /* opaque: a captured sequence of compute calls, ready to replay */
 
 typedef enum {
     ORTHRUS_OK = 0,
@@ -203,6 +204,29 @@ orthrus_status orthrus_sampling_consensus_commit(orthrus_ctx *ctx, const orthrus
                                                  int32_t *accept_len, int32_t *num_committed,
                                                  int32_t *out_tokens, int32_t *next_anchor,
                                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Replay of a fixed sequence of compute calls as one HIP graph.  A decode cycle is two passes of the
+ * whole layer stack plus the consensus (Section 3.2-3.3; Section 4 counts "forward passes"), i.e. tens
+ * of short launches whose arguments do not change from cycle to cycle when the caller reuses its
+ * buffers; replaying them as a graph removes the per-launch host cost and most of the gaps between
+ * kernels.  Usage: orthrus_graph_begin(ctx, stream); any number of orthrus_dual_view_attn /
+ * orthrus_consensus_commit / orthrus_sampling_consensus_commit calls on that same stream (nothing
+ * runs, the launches are recorded; the entry points launch kernels only, so all of them may be
+ * recorded); orthrus_graph_end(ctx, stream, &g); then orthrus_graph_launch(g, stream) once per cycle.
+ *   - `stream` must be a created stream (not NULL).  The calling thread must not allocate or free
+ *     device memory between begin and end.
+ *   - Every pointer and every orthrus_params field is frozen into the graph: new inputs are written
+ *     into the same buffers before each launch, and max_seq_len must bound the lengths of every
+ *     replay.  Sequence lengths and caches live on the device and keep evolving across replays.
+ *   - Per-kernel timing must be off while recording.
+ * The graph is independent of the context afterwards, except that its kernels report device errors
+ * into the context's error word: destroy the graph before the context.
+ */
+orthrus_status orthrus_graph_begin(orthrus_ctx *ctx, void *stream);
+orthrus_status orthrus_graph_end(orthrus_ctx *ctx, void *stream, orthrus_graph **out);
+orthrus_status orthrus_graph_launch(orthrus_graph *graph, void *stream);
+orthrus_status orthrus_graph_destroy(orthrus_graph *graph);
 
 /*
  * Per-kernel timing of orthrus_dual_view_attn, for measurement (Section 4 reports throughput; this is

@@ -27,6 +27,7 @@ EXPORTED = [
     "orthrus_create", "orthrus_destroy", "orthrus_status_string", "orthrus_attn_workspace_bytes",
     "orthrus_consensus_workspace_bytes", "orthrus_sampling_workspace_bytes", "orthrus_attn_num_splits",
     "orthrus_dual_view_attn", "orthrus_consensus_commit", "orthrus_sampling_consensus_commit",
+    "orthrus_graph_begin", "orthrus_graph_end", "orthrus_graph_launch", "orthrus_graph_destroy",
     "orthrus_attn_timing", "orthrus_attn_timing_read", "orthrus_last_device_error",
 ]
 
@@ -86,6 +87,14 @@ def _load() -> ctypes.CDLL:
     lib.orthrus_sampling_consensus_commit.restype = ctypes.c_int
     lib.orthrus_sampling_consensus_commit.argtypes = [vp, pp, ctypes.c_float, vp, vp, i32p, vp, vp, vp, vp, vp, vp,
                                                       i32p, i32p, i32p, i32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+    lib.orthrus_graph_begin.restype = ctypes.c_int
+    lib.orthrus_graph_begin.argtypes = [vp, vp]
+    lib.orthrus_graph_end.restype = ctypes.c_int
+    lib.orthrus_graph_end.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_void_p)]
+    lib.orthrus_graph_launch.restype = ctypes.c_int
+    lib.orthrus_graph_launch.argtypes = [vp, vp]
+    lib.orthrus_graph_destroy.restype = ctypes.c_int
+    lib.orthrus_graph_destroy.argtypes = [vp]
     lib.orthrus_attn_timing.restype = ctypes.c_int
     lib.orthrus_attn_timing.argtypes = [vp, ctypes.c_int]
     lib.orthrus_attn_timing_read.restype = ctypes.c_int
@@ -206,6 +215,32 @@ def orthrus_sampling_consensus_commit(ctx, p: orthrus_params, temperature: float
     if check and st != ORTHRUS_OK:
         raise OrthrusError(st, "orthrus_sampling_consensus_commit")
     return st
+
+
+def orthrus_graph_begin(ctx, stream) -> None:
+    st = _lib.orthrus_graph_begin(ctx, _stream_handle(stream))
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_graph_begin")
+
+
+def orthrus_graph_end(ctx, stream) -> int:
+    g = ctypes.c_void_p()
+    st = _lib.orthrus_graph_end(ctx, _stream_handle(stream), ctypes.byref(g))
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_graph_end")
+    return g.value
+
+
+def orthrus_graph_launch(graph, stream=None) -> None:
+    st = _lib.orthrus_graph_launch(graph, _stream_handle(stream))
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_graph_launch")
+
+
+def orthrus_graph_destroy(graph) -> None:
+    st = _lib.orthrus_graph_destroy(graph)
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_graph_destroy")
 
 
 def orthrus_attn_timing(ctx, enable: bool) -> None:

@@ -8,6 +8,11 @@
 #include <new>
 #include <vector>
 
+struct orthrus_graph {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+
 struct orthrus_ctx {
     int device;
     int num_cus;
@@ -228,6 +233,52 @@ orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p,
         }
     }
     return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
+orthrus_status orthrus_graph_begin(orthrus_ctx *ctx, void *stream)
+{
+    if (!ctx || !stream) return ORTHRUS_EINVAL;  // the NULL stream cannot be captured
+    if (ctx->timing) return ORTHRUS_EINVAL;      // timed launches create events: not under capture
+    return hipStreamBeginCapture((hipStream_t)stream, hipStreamCaptureModeThreadLocal) == hipSuccess ? ORTHRUS_OK
+                                                                                                     : ORTHRUS_EHIP;
+}
+
+orthrus_status orthrus_graph_end(orthrus_ctx *ctx, void *stream, orthrus_graph **out)
+{
+    if (!ctx || !stream || !out) return ORTHRUS_EINVAL;
+    *out = nullptr;
+    hipGraph_t graph = nullptr;
+    if (hipStreamEndCapture((hipStream_t)stream, &graph) != hipSuccess || !graph) return ORTHRUS_EHIP;
+    hipGraphExec_t exec = nullptr;
+    if (hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess) {
+        hipGraphDestroy(graph);
+        return ORTHRUS_EHIP;
+    }
+    orthrus_graph *g = new (std::nothrow) orthrus_graph;
+    if (!g) {
+        hipGraphExecDestroy(exec);
+        hipGraphDestroy(graph);
+        return ORTHRUS_EINVAL;
+    }
+    g->graph = graph;
+    g->exec = exec;
+    *out = g;
+    return ORTHRUS_OK;
+}
+
+orthrus_status orthrus_graph_launch(orthrus_graph *graph, void *stream)
+{
+    if (!graph || !graph->exec) return ORTHRUS_EINVAL;
+    return hipGraphLaunch(graph->exec, (hipStream_t)stream) == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
+orthrus_status orthrus_graph_destroy(orthrus_graph *graph)
+{
+    if (!graph) return ORTHRUS_EINVAL;
+    hipError_t e1 = graph->exec ? hipGraphExecDestroy(graph->exec) : hipSuccess;
+    hipError_t e2 = graph->graph ? hipGraphDestroy(graph->graph) : hipSuccess;
+    delete graph;
+    return (e1 == hipSuccess && e2 == hipSuccess) ? ORTHRUS_OK : ORTHRUS_EHIP;
 }
 
 orthrus_status orthrus_attn_timing(orthrus_ctx *ctx, int enable)

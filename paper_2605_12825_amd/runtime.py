@@ -107,3 +107,90 @@ class DecodeStep:
 
     def device_error(self, stream=None) -> int:
         return B.orthrus_last_device_error(self.ctx, stream)
+
+
+class DecodeStack:
+    """One decode cycle over a stack of layers, eagerly or as a replayed HIP graph.
+
+    The cycle is the paper's: the diffusion view's pass through every layer, the AR view's
+    verification pass through every layer, then the consensus and the commit of the accepted
+    tokens' K/V into every layer's cache (Section 3.2-3.3, Fig. 2(b)).  Only the attention of each
+    layer is computed here; whatever produces a layer's queries and block K/V writes them into
+    this object's static buffers (`q_diff[l]`, `k_blk_diff[l]`, ... `ar_logits`, `draft_tokens`).
+    Argument marshalling only: the loop below calls the C ABI once per layer and view.
+    """
+
+    def __init__(self, *, num_layers, batch, num_q_heads, num_kv_heads, head_dim, block_k, page_size,
+                 k_pool, v_pool, page_table, seq_lens, max_seq_len, vocab, num_splits=0, temperature=0.0,
+                 device=0):
+        if k_pool.dim() != 5 or k_pool.shape[0] != num_layers or not k_pool.is_contiguous():
+            raise ValueError("pools must be contiguous [layers, pages, H_kv, P, d]")
+        L, pages, H, P, d = k_pool.shape
+        self.num_layers, self.temperature = num_layers, float(temperature)
+        self.k_pool, self.v_pool, self.page_table, self.seq_lens = k_pool, v_pool, page_table, seq_lens
+        self.step = DecodeStep(batch=batch, num_q_heads=num_q_heads, num_kv_heads=num_kv_heads, head_dim=head_dim,
+                               block_k=block_k, page_size=page_size, max_pages_per_seq=page_table.shape[1],
+                               max_seq_len=max_seq_len, num_pages=pages, vocab=vocab, num_layers=num_layers,
+                               num_splits=num_splits, device=device,
+                               pool_strides=(pages * H * P * d, H * P * d, P * d, d))
+        dev = self.step.device
+        blk = (num_layers, batch, block_k, num_kv_heads, head_dim)
+        qs = (num_layers, batch, block_k, num_q_heads, head_dim)
+        i16 = dict(dtype=torch.int16, device=dev)
+        self.q_diff, self.q_ar = torch.zeros(qs, **i16), torch.zeros(qs, **i16)
+        self.k_blk_diff, self.v_blk_diff = torch.zeros(blk, **i16), torch.zeros(blk, **i16)
+        self.k_blk_ar, self.v_blk_ar = torch.zeros(blk, **i16), torch.zeros(blk, **i16)
+        self.out_diff, self.out_ar = torch.zeros(qs, **i16), torch.zeros(qs, **i16)
+        self.ar_logits = torch.zeros((batch, block_k, vocab), dtype=torch.float32, device=dev)
+        self.draft_tokens = torch.zeros((batch, block_k), dtype=torch.int32, device=dev)
+        if self.temperature > 0:
+            self.diff_logits = torch.zeros_like(self.ar_logits)
+            self.accept_u = torch.zeros((batch, block_k), dtype=torch.float32, device=dev)
+            self.gumbel = torch.zeros((batch, vocab), dtype=torch.float32, device=dev)
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.accept_len, self.num_committed, self.next_anchor = (torch.zeros((batch,), **i32) for _ in range(3))
+        self.out_tokens = torch.zeros((batch, block_k), **i32)
+        self.graph = None
+        self.graph_stream = None
+
+    def cycle(self, stream=None) -> None:
+        """Issues the whole cycle on `stream` (default: the current stream)."""
+        s = self.step
+        for view, q, kb, vb, out in ((0, self.q_diff, self.k_blk_diff, self.v_blk_diff, self.out_diff),
+                                     (1, self.q_ar, self.k_blk_ar, self.v_blk_ar, self.out_ar)):
+            for l in range(self.num_layers):
+                s.attn(view, q[l], kb[l], vb[l], self.k_pool[l], self.v_pool[l], self.page_table, self.seq_lens,
+                       out[l], None, stream)
+        if self.temperature > 0:
+            s.sampling_consensus_commit(self.temperature, self.ar_logits, self.diff_logits, self.draft_tokens,
+                                        self.accept_u, self.gumbel, self.k_blk_ar, self.v_blk_ar, self.k_pool,
+                                        self.v_pool, self.page_table, self.seq_lens, self.accept_len,
+                                        self.num_committed, self.out_tokens, self.next_anchor, stream)
+        else:
+            s.consensus_commit(self.ar_logits, self.draft_tokens, self.k_blk_ar, self.v_blk_ar, self.k_pool,
+                               self.v_pool, self.page_table, self.seq_lens, self.accept_len, self.num_committed,
+                               self.out_tokens, self.next_anchor, stream)
+
+    def capture(self) -> None:
+        """Records one cycle into a HIP graph (on a stream of its own, default priority)."""
+        if self.graph is not None:
+            raise RuntimeError("already captured")
+        torch.cuda.synchronize(self.step.device)
+        self.graph_stream = torch.cuda.Stream(device=self.step.device)
+        B.orthrus_graph_begin(self.step.ctx, self.graph_stream)
+        try:
+            self.cycle(self.graph_stream)
+        finally:
+            self.graph = B.orthrus_graph_end(self.step.ctx, self.graph_stream)
+
+    def replay(self, stream=None) -> None:
+        if self.graph is None:
+            raise RuntimeError("capture() first")
+        B.orthrus_graph_launch(self.graph, self.graph_stream if stream is None else stream)
+
+    def close(self) -> None:
+        if self.graph is not None:
+            torch.cuda.synchronize(self.step.device)
+            B.orthrus_graph_destroy(self.graph)
+            self.graph = None
+        self.step.close()
