@@ -46,6 +46,11 @@ def parse():
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="0: greedy consensus (Eq. 8); > 0: lossless sampling consensus at that temperature")
     ap.add_argument("--paging", default="", help="override the workload's page-table layout: contiguous|shuffled|scattered")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="> 1 (or --graph): time whole decode cycles over a stack of layers: the diffusion pass "
+                         "through every layer, the AR pass through every layer, consensus + commit into all of them")
+    ap.add_argument("--graph", action="store_true", help="replay each cycle as one HIP graph instead of eager launches")
+    ap.add_argument("--block-k", type=int, default=0, help="override the workload's block size K (latency-vs-K sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-every", type=int, default=8,
                     help="time the kernels of every Nth timed step with HIP events (0: never)")
@@ -89,6 +94,92 @@ def cpu_baseline(w, cache, host_sets, cons_sets):
                       (len(times), w.batch, " + consensus" if cons_sets else "", mean)}
 
 
+def run_stack(args, torch, rt, w, cache, host_sets, cons_sets, splits):
+    """Whole decode cycles over --layers layers (Fig. 2(b)): eager launches or one HIP graph per cycle.
+
+    The layers share one layer's synthetic cache and block inputs (replicated on the device: values do
+    not change the timing); the N_SETS rotating input sets are N_SETS stacks over the same pools.
+    """
+    T, nl = args.temperature, args.layers
+    B, K = w.batch, w.block_k
+    D = rt.to_device_bits
+    rep = lambda t: t.unsqueeze(0).repeat(nl, *([1] * t.dim())).contiguous()
+    k_pool, v_pool = rep(D(cache["k_pool"])), rep(D(cache["v_pool"]))
+    page_table, seq_lens = D(cache["page_table"]), D(cache["seq_lens"])
+    cap = min(w.capacity_tokens(), cache["page_table"].shape[1] * w.page_size)
+    stacks = []
+    for i in range(N_SETS):
+        st = rt.DecodeStack(num_layers=nl, batch=B, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
+                            head_dim=w.head_dim, block_k=K, page_size=w.page_size, k_pool=k_pool, v_pool=v_pool,
+                            page_table=page_table, seq_lens=seq_lens, max_seq_len=cap, vocab=w.vocab,
+                            num_splits=splits, temperature=T)
+        d, a = host_sets[i]
+        for name, blk, key in (("q_diff", d, "q"), ("k_blk_diff", d, "k_blk"), ("v_blk_diff", d, "v_blk"),
+                               ("q_ar", a, "q"), ("k_blk_ar", a, "k_blk"), ("v_blk_ar", a, "v_blk")):
+            getattr(st, name).copy_(rep(D(blk[key])))
+        cs = cons_sets[i]
+        for name in ("ar_logits", "draft_tokens") + (("diff_logits", "accept_u", "gumbel") if T > 0 else ()):
+            getattr(st, name).copy_(D(cs[name]))
+        stacks.append(st)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    if args.graph:
+        for st in stacks:
+            st.capture()
+    with torch.cuda.stream(stream):
+        def run(i):
+            st = stacks[i % N_SETS]
+            if args.graph:
+                st.replay(stream)
+            else:
+                st.cycle(stream)
+        for i in range(args.warmup):
+            run(i)
+        stream.synchronize()
+        lens_before = seq_lens.cpu().numpy().astype(np.int64)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(args.steps):
+            run(args.warmup + i)
+        e1.record(stream)
+        stream.synchronize()
+    total_ms = e0.elapsed_time(e1)
+    lens_after = seq_lens.cpu().numpy().astype(np.int64)
+    err = max(abs(st.step.device_error()) for st in stacks)
+    if err != 0:
+        log("bench.py: device error word -%d after the timed region" % err)
+        sys.exit(4)
+    ms = total_ms / args.steps
+    mean_tokens = 0.5 * (lens_before.sum() + lens_after.sum())
+    kv_bytes = mean_tokens * w.num_kv_heads * 2 * w.head_dim * 2          # one attention call
+    committed = float((lens_after - lens_before).sum()) / args.steps       # tokens per cycle, whole batch
+    whole = 2 * nl * kv_bytes / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "draft+verify block-attn steps/s and achieved KV-read HBM TB/s (1 MI355X)",
+        "value": round(1000.0 / ms, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "description": w.description, "batch": B, "num_q_heads": w.num_q_heads,
+                   "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim, "block_k": K,
+                   "context": int(lens_before.max()), "page_size": w.page_size, "vocab": w.vocab,
+                   "num_splits": stacks[0].step.num_splits, "layers": nl, "graph": bool(args.graph), "temperature": T,
+                   "step": "one decode cycle: %d diffusion attn + %d AR verify attn + consensus + commit into "
+                           "%d layers" % (nl, nl, nl)},
+        "roofline": {"bound": "hbm", "achieved": round(whole, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(whole / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "whole cycle (all attention launches + consensus + commit), not one kernel: "
+                               "algorithmic KV bytes of the %d attention calls over the cycle time" % (2 * nl),
+                     "avg_launch_us": round(ms * 1e3 / (2 * nl), 2), "algorithmic_bytes_per_launch": int(kv_bytes)},
+        "detail": {"tokens_per_s": round(committed / (ms * 1e-3), 1),
+                   "tokens_committed_per_cycle_per_sequence": round(committed / max(B, 1), 3),
+                   "tokens_per_forward_pass": round(committed / max(B, 1) / 2.0, 3),
+                   "cycle_us_per_layer": round(ms * 1e3 / nl, 2)},
+    }
+    for st in stacks:
+        st.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -113,6 +204,8 @@ def main():
 
     total_steps = args.warmup + args.steps
     w = WORKLOADS[args.workload]
+    if args.block_k > 0:
+        w = w.with_(block_k=args.block_k)
     # capacity: the cache grows by <= K tokens per committed step (never, for a workload without consensus)
     w = w.with_(steps=(total_steps + 1) if w.vocab else 0)
     if args.paging:
@@ -132,6 +225,12 @@ def main():
     else:
         cons_sets = [make_consensus_case(w, w.seed * 1000 + 10 * i + 3) for i in range(N_SETS)]
     log("generated %s inputs in %.1f s" % (w.name, time.perf_counter() - t_gen))
+    if args.layers > 1 or args.graph:
+        if not w.vocab:
+            log("bench.py: --layers/--graph time whole cycles and need a workload with a consensus step")
+            sys.exit(2)
+        run_stack(args, torch, rt, w, cache, host_sets, cons_sets, splits)
+        return
 
     dev = torch.device("cuda:0")
     D = rt.to_device_bits
@@ -190,6 +289,7 @@ def main():
         # let the library create the events the sampled steps will need now, outside the timed region
         # (it recycles them after a read); these untimed calls leave the cache as it is
         step.attn_timing(True)
+        step.set_max_seq_len(min(cap, len0 + (args.warmup if w.vocab else 0) * K))
         d, a = sets[0]
         for _ in range((args.steps + args.event_every - 1) // args.event_every):
             step.attn(0, d["q"], d["k_blk"], d["v_blk"], k_pool, v_pool, page_table, seq_lens, o_d)
