@@ -6,14 +6,16 @@
 //   grid   = one workgroup per (split, KV head g, sequence b).  A workgroup streams cache tokens
 //            [split*chunk, min(L_b, (split+1)*chunk)) of KV head g once and serves all R = G*K
 //            query rows that share that KV head (G query heads x K block rows).
-//   waves  = W per workgroup, one per block of 32 query rows (W = 1, 2, 4 or 8).  Every wave reads
-//            every K/V tile, so the tile stream is shared: 32-token tiles go from global memory
-//            straight into an NS-stage LDS ring (global_load_lds_dwordx4: coalesced 16-byte loads,
-//            one 256-byte row per 16 lanes; the waves split a tile's load instructions among them),
-//            NS-1 tiles ahead of the one being computed, with one workgroup barrier per tile.
-//            Workgroups are small (LDS ring of ~50 KB, <= 256 registers per lane) so that several
-//            are resident per CU and one workgroup's start-up and write-out overlap the others'
-//            streaming.
+//            Workgroups are numbered with the sequence index fastest and the KV head slowest
+//            (consecutive ids go to different XCDs; see the kernel).
+//   waves  = W compute waves per workgroup, one per block of 32 query rows (W = 1, 2, 4 or 8), plus
+//            one loader wave.  Every compute wave reads every K/V tile, so the tile stream is shared:
+//            the loader sends 32-token tiles from global memory straight into an NS-stage LDS ring
+//            (global_load_lds_dwordx4: coalesced 16-byte loads, one 256-byte row per 16 lanes), NS-1
+//            tiles ahead of the one being computed, with one workgroup barrier per tile.  The launch
+//            plan aims at one workgroup per CU: that keeps ~32 KB in flight per CU, which already
+//            saturates HBM, and shares the bandwidth evenly between the XCDs (with twice as much in
+//            flight some XCDs finish 20 % later than others).
 //   MFMA   = v_mfma_f32_32x32x16_bf16 for both contractions, on the transposed problem:
 //            S^T[token][row] = K_tile . Q^T   (A = K from LDS, B = Q held in registers)
 //            O^T[d][row]    += V^T . P^T      (A = V through the LDS transpose read, B = P)
@@ -110,31 +112,29 @@ struct AttnGeom {
 };
 
 // D head_dim, W compute waves (= 32-row blocks) per workgroup, NS LDS stages.
-// LOADER: the workgroup has one more wave that issues every tile load and does nothing else.  A wave
-// that issues global->LDS loads is held up while the memory pipeline takes them (streaming 2 MB per CU
-// costs the issuing waves about as long as the arithmetic on it does), so when the compute waves issue
-// their own loads the two costs add up; with a dedicated loader wave they overlap.  Used whenever
-// W + 1 waves leave room for at least one workgroup per CU at two waves per SIMD (W <= 4).
-template <int D, int W, int NS, bool LOADER>
-__global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_kernel(const AttnArgs a)
+//
+// A workgroup has W compute waves and one loader wave that issues every tile load and does nothing
+// else.  A wave that issues global->LDS loads is held up while the memory pipeline takes them
+// (streaming 2 MB per CU costs the issuing wave about as long as the arithmetic on it costs a compute
+// wave), so when compute waves issue their own loads the two costs add up; with a dedicated loader
+// wave they overlap.  The compute waves stay below 168 registers, so W + 1 <= 9 waves fit a CU at
+// three waves per SIMD.
+template <int D, int W, int NS>
+__global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnArgs a)
 {
     using Gm = AttnGeom<D>;
     constexpr int CH = Gm::CH, ROWB = Gm::ROWB, RPI = Gm::RPI, NI = Gm::NI, GS = Gm::GS;
     constexpr int TILE_B = Gm::TILE_B, STAGE_B = Gm::STAGE_B, KSTEPS = Gm::KSTEPS, DBLK = Gm::DBLK;
-    constexpr int LPT = 2 * NI;            // load instructions per tile (K groups then V groups)
-    constexpr int IW = LOADER ? 1 : W;     // waves that issue them
-    constexpr int MY = LPT / IW;           // loads per tile per issuing wave
-    static_assert(LPT % IW == 0, "issuing waves must split a tile's loads evenly");
+    constexpr int LPT = 2 * NI;  // load instructions per tile (K groups then V groups), all by the loader wave
     static_assert(NS >= 2 && NS <= 4, "stage count");
-    static_assert((NS - 2) * MY < 64, "outstanding loads must fit the vmcnt field");
+    static_assert((NS - 2) * LPT < 64, "outstanding loads must fit the vmcnt field");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool loader = LOADER && wave == W;
-    const int iw = LOADER ? 0 : wave;      // index among the issuing waves
+    const bool loader = wave == W;
     const int col = lane & 31, h = lane >> 5;
     // Workgroup id -> (sequence, split, KV head) with the sequence index fastest and the head slowest.
     // Consecutive workgroup ids go to different XCDs; a head's rows sit at a fixed offset inside every
@@ -197,7 +197,7 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
             if (ts + 16 < t_end) p1 = pt_row[(ts + 16) >> a.page_shift];
         }
     };
-    // Start this wave's share of the loads of tile t (cache tile, or the in-block tile when
+    // Start the loads of tile t (cache tile, or the in-block tile when
     // t == n_cache) into ring stage t % NS.  A full cache tile takes the cheap address form: page, head
     // and row group go into a wave-uniform base (scalar arithmetic), the lane adds one loop-invariant
     // byte offset.  In the last, ragged cache tile rows past the end repeat the last valid row (finite
@@ -217,8 +217,8 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
             if (ts + 32 <= t_end) {
                 const int tsp = ts & (P - 1);
 #pragma unroll
-                for (int e = 0; e < MY; ++e) {
-                    const int id = iw + e * IW;               // 0..LPT-1: K groups, then V groups
+                for (int e = 0; e < LPT; ++e) {
+                    const int id = e;               // 0..LPT-1: K groups, then V groups
                     const int u = id % NI;
                     const int page = (u * RPI < 16) ? p0 : p1;
                     const int tin = (tsp + u * RPI) & (P - 1);
@@ -227,8 +227,8 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
                 }
             } else {
 #pragma unroll
-                for (int e = 0; e < MY; ++e) {
-                    const int id = iw + e * IW;
+                for (int e = 0; e < LPT; ++e) {
+                    const int id = e;
                     const int u = id % NI;
                     const uint16_t *pool = id < NI ? a.k_pool : a.v_pool;
                     const int tok = u * RPI + ld_tok;
@@ -241,8 +241,8 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
             }
         } else {
 #pragma unroll
-            for (int e = 0; e < MY; ++e) {
-                const int id = iw + e * IW;
+            for (int e = 0; e < LPT; ++e) {
+                const int id = e;
                 const int u = id % NI;
                 const uint16_t *blk = id < NI ? a.k_blk : a.v_blk;
                 const int tok = u * RPI + ld_tok;
@@ -253,10 +253,9 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
         }
     };
 
-    // One step of the load pipeline, run by every issuing wave once per tile i, around the tile's
-    // workgroup barrier: before the barrier this wave's loads of tile i are complete; after it, so are
-    // everybody's, and every wave is done reading stage (i-1) % NS, which is refilled with tile
-    // i+NS-1 while tile i is computed.
+    // One step of the load pipeline, run by the loader wave once per tile i, around the tile's workgroup
+    // barrier: before the barrier the loads of tile i are complete; after it every compute wave is done
+    // reading stage (i-1) % NS, which is refilled with tile i+NS-1 while tile i is computed.
     int np0 = 0, np1 = 0;  // page ids of the next tile to be issued
     auto pipeline_fill = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -268,8 +267,8 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
     };
     auto pipeline_step = [&](int i) __attribute__((always_inline)) {
         const int ahead = min(NS - 2, n_tiles - 1 - i);  // tiles issued after tile i so far
-        if (ahead >= 2) wait_vmcnt<2 * MY>();
-        else if (ahead == 1) wait_vmcnt<MY>();
+        if (ahead >= 2) wait_vmcnt<2 * LPT>();
+        else if (ahead == 1) wait_vmcnt<LPT>();
         else wait_vmcnt<0>();
         wg_barrier();
         if (i + NS - 1 < n_tiles) issue_tile(i + NS - 1, np0, np1);
@@ -282,10 +281,9 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
         for (int i = 0; i < n_tiles; ++i) pipeline_step(i);
         return;
     }
-    if (!LOADER) pipeline_fill();
 
-    // queries: B operand of S^T = K.Q^T, lane holds row `col` of this wave's block, d = 16*kk + 8*h .. +7
-    // (fetched while the first tiles are in flight)
+    // ---- compute waves.  Queries: B operand of S^T = K.Q^T, lane holds row `col` of this wave's block,
+    // d = 16*kk + 8*h .. +7 (fetched while the loader's first tiles are in flight)
     Frag qf[KSTEPS];
     int irow;
     const int ridx = wave * 32 + col;
@@ -300,10 +298,7 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) qf[kk].u = make_uint4(0, 0, 0, 0);
     }
-    // Every vector load the compiler knows about (the queries) is waited for here, before the loop:
-    // inside the loop only the hand-issued tile loads are outstanding, so the compiler adds no vmcnt
-    // wait of its own there (such a wait would also drain the tiles that are being prefetched).
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0), other counters untouched
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the queries are in registers before the loop starts
 
     f32x16 o[DBLK];
 #pragma unroll
@@ -335,8 +330,7 @@ __global__ void __launch_bounds__(64 * (W + (LOADER ? 1 : 0)), 2) attn_split_ker
     // ---- main loop: one barrier per tile
     int stage = 0;  // ring slot of tile i (= i % NS)
     for (int i = 0; i < n_tiles; ++i) {
-        if (LOADER) wg_barrier();
-        else pipeline_step(i);
+        wg_barrier();
 
         // LDS addresses of this tile's operands: one add per base, the rest are instruction offsets
         const uint32_t st_addr = smem_lds + (uint32_t)stage * STAGE_B;
@@ -529,11 +523,6 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
 #define ORTHRUS_ATTN_STAGES 3
 #endif
 constexpr int kStages = ORTHRUS_ATTN_STAGES;  // LDS ring depth (2..4)
-#ifndef ORTHRUS_ATTN_LOADER_MAX_W
-#define ORTHRUS_ATTN_LOADER_MAX_W 8
-#endif
-constexpr int kMaxLoaderWaves = ORTHRUS_ATTN_LOADER_MAX_W;  // workgroups of up to this many compute waves get a loader wave
-
 static size_t lds_need(int head_dim)
 {
     return (size_t)kStages * (head_dim == 128 ? AttnGeom<128>::STAGE_B : AttnGeom<64>::STAGE_B);
@@ -550,12 +539,10 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     plan->rows_padded = W * 32;
     plan->lds_bytes = lds_need(head_dim);
     const int64_t units = (int64_t)batch * num_kv_heads;
-    // workgroups resident per CU: LDS ring size, and 12 waves with a loader wave (3 per SIMD: the
-    // compute waves stay below 168 registers) or 8 waves without (2 per SIMD at <= 256 registers)
-    const bool has_loader = W <= kMaxLoaderWaves;
-    const int wg_waves = W + (has_loader ? 1 : 0), cu_waves = has_loader ? 12 : 8;
+    // workgroups resident per CU: LDS ring size, and 12 waves (3 per SIMD: the kernel stays below 168
+    // registers) of W compute waves + the loader wave each
     int per_cu = (int)(160 * 1024 / plan->lds_bytes);
-    if (per_cu > cu_waves / wg_waves) per_cu = cu_waves / wg_waves;
+    if (per_cu > 12 / (W + 1)) per_cu = 12 / (W + 1);
     if (per_cu < 1) per_cu = 1;
     int splits;
     if (requested_splits > 0) {
@@ -563,9 +550,8 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     } else {
         // Pick the split count with a small cost model (times in microseconds), using max_seq_len for
         // every sequence: workgroups run in rounds of `slots`; a round streams at the practical HBM
-        // rate once every CU holds a workgroup with a loader wave (or, without one, at least 4 waves
-        // that stream and compute in turns); every split beyond the first writes and re-reads an fp32
-        // partial (rows x d x 4 bytes) and adds the combine launch.
+        // rate once every CU holds a workgroup; every split beyond the first writes and re-reads an
+        // fp32 partial (rows x d x 4 bytes) and adds the combine launch.
         const double kRate = 6.0e6;          // bytes per microsecond (practical streaming ceiling)
         const double kRound = 5.0, kCombine = 8.0;
         const int64_t slots = (int64_t)num_cus * per_cu;
@@ -582,9 +568,7 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
                 const int64_t now = left < slots ? left : slots;
                 // workgroups spread over the CUs first; a CU that streams gets its share of the HBM rate
                 const double active = now < num_cus ? (double)now : (double)num_cus;
-                double per_cu_waves = W <= kMaxLoaderWaves ? 1.0 : (double)now * W / active / 4.0;
-                if (per_cu_waves > 1.0) per_cu_waves = 1.0;
-                const double f = active / num_cus * per_cu_waves;
+                const double f = active / num_cus;
                 t += kRound + per_wg * now / (kRate * f);
             }
             if (t < best * 0.98) { best = t; splits = s; }  // prefer fewer splits unless clearly better
@@ -609,11 +593,10 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
 template <int D, int W>
 static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStream_t stream, AttnLaunchEvents *ev)
 {
-    constexpr bool kLoader = W <= kMaxLoaderWaves;
-    auto kern = attn_split_kernel<D, W, kStages, kLoader>;
+    auto kern = attn_split_kernel<D, W, kStages>;
     const bool timed = ev && ev->on;
     dim3 grid((unsigned)plan.num_splits * (unsigned)a.num_kv_heads * (unsigned)a.batch);
-    dim3 block(64 * (W + (kLoader ? 1 : 0)));
+    dim3 block(64 * (W + 1));
     if (timed) {
         hipExtLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, ev->start[0], ev->stop[0], 0, a);
         ev->used[0] = true;
