@@ -54,6 +54,10 @@ def _load():
         lib.orthrus_oracle_sampling_consensus_commit.argtypes = [
             i32, i32, i32, f64, i32, i32, i32, i32, i32, i64,
             p, p, p, p, p, p, p, p, p, i64, i64, i64, i64, p, p, p, p, p, p, p, p]
+        lib.orthrus_oracle_prefill_attn.restype = ctypes.c_int
+        lib.orthrus_oracle_prefill_attn.argtypes = [
+            i32, i32, i32, i32, i32, i32, i32, i64, f64,
+            p, p, p, p, p, p, i64, i64, i64, p, p, p]
         _lib = lib
     return _lib
 
@@ -104,6 +108,37 @@ def dual_view_attn(view: int, sm_scale: float, q: np.ndarray, k_blk: np.ndarray,
     if rc != 0:
         raise RuntimeError("orthrus_oracle_dual_view_attn failed with status %d" % rc)
     return (out, lse) if want_lse else out
+
+
+def prefill_attn(sm_scale: float, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, new_lens: np.ndarray,
+                 k_pool: np.ndarray, v_pool: np.ndarray, page_table: np.ndarray, seq_lens: np.ndarray,
+                 allow_capacity_error: bool = False):
+    """AR prefill of one layer: appends the new tokens' K/V, causal attention of each over the cache.
+
+    ``q`` is ``[B,T,H_q,d]``, ``k_new``/``v_new`` ``[B,T,H_kv,d]`` (bf16 bits), ``new_lens[b] <= T``;
+    pools and ``seq_lens`` are updated in place.  Returns fp64 ``out[B,T,H_q,d]`` (rows past
+    ``new_lens[b]`` are NaN) and the status (0, or -4 when allowed).
+    """
+    lib = _load()
+    B, T, Hq, d = q.shape
+    Hkv = k_new.shape[2]
+    for a, n in ((q, "q"), (k_new, "k_new"), (v_new, "v_new"), (k_pool, "k_pool"), (v_pool, "v_pool")):
+        _check(a, np.uint16, n)
+    _check(page_table, np.int32, "page_table"); _check(seq_lens, np.int32, "seq_lens")
+    _check(new_lens, np.int32, "new_lens")
+    if k_new.shape != (B, T, Hkv, d) or v_new.shape != k_new.shape:
+        raise ValueError("new K/V shape mismatch")
+    if k_pool.shape != v_pool.shape or k_pool.shape[1] != Hkv or k_pool.shape[3] != d:
+        raise ValueError("pool shape mismatch")
+    sp, sh, st = _pool_strides(k_pool)
+    out = np.full((B, T, Hq, d), np.nan, dtype=np.float64)
+    rc = lib.orthrus_oracle_prefill_attn(
+        B, T, Hq, Hkv, d, k_pool.shape[2], page_table.shape[1], k_pool.shape[0], float(sm_scale),
+        _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(new_lens), _ptr(k_pool), _ptr(v_pool), sp, sh, st,
+        _ptr(page_table), _ptr(seq_lens), _ptr(out))
+    if rc != 0 and not (rc == -4 and allow_capacity_error):
+        raise RuntimeError("orthrus_oracle_prefill_attn failed with status %d" % rc)
+    return out, rc
 
 
 def consensus_commit(ar_logits: np.ndarray, draft_tokens: np.ndarray,

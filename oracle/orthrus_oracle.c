@@ -28,6 +28,12 @@
  *                                     rejected one is replaced by a draw from the normalised positive
  *                                     part of p - q), applied left to right over the block.
  *
+ *   orthrus_oracle_prefill_attn       Section 3.1, first paragraph, and Section 3.3: the frozen AR view's
+ *                                     ordinary causal self-attention over the context ("pre-filling"),
+ *                                     which is what builds the shared K/V cache: token t attends tokens
+ *                                     0..t (textbook causal softmax attention, Section 2.1), and its K/V
+ *                                     row is appended to the cache.
+ *
  * Readings taken where the paper is silent (each is a stated reading, not a derivation):
  *   - the cache holds tokens strictly before the anchor x_t (Section 3.3: K_AR^{<t}); the
  *     anchor's own K/V is in-block row 0;
@@ -165,6 +171,94 @@ int orthrus_oracle_dual_view_attn(
             }
             free(s);
         }
+    }
+    return status;
+}
+
+/*
+ * AR prefill of one attention layer (Section 3.1: the AR view processes the context with standard causal
+ * self-attention and leaves its K/V in the cache).  Per sequence b with L = seq_lens[b] cached tokens
+ * and n = new_lens[b] new tokens (0 <= n <= T):
+ *   cache rows L..L+n-1 of KV head g  <-  k_new[b,i,g,:], v_new[b,i,g,:]      i = 0..n-1
+ *   out[b,i,h,:] = sum_j softmax_j( sm_scale * <q[b,i,h,:], K_j> ) V_j  over cache tokens j = 0..L+i
+ *   seq_lens[b] = L + n
+ * i.e. the new token at position L+i sees everything before it and itself.  Rows i >= n of out are left
+ * untouched.  q, out [B,T,H_q,d]; k_new, v_new [B,T,H_kv,d]; pools and page table as above (updated in
+ * place).  If a needed page of sequence b is not mapped, that sequence's cache, length and output are left
+ * untouched and -4 is returned after the other sequences were processed.  Returns 0, -1 or -4.
+ */
+int orthrus_oracle_prefill_attn(
+    int batch, int max_new, int num_q_heads, int num_kv_heads, int head_dim,
+    int page_size, int max_pages_per_seq, int64_t num_pages, double sm_scale,
+    const uint16_t *q, const uint16_t *k_new, const uint16_t *v_new, const int32_t *new_lens,
+    uint16_t *k_pool, uint16_t *v_pool,
+    int64_t stride_page, int64_t stride_head, int64_t stride_tok,
+    const int32_t *page_table, int32_t *seq_lens, double *out)
+{
+    if (batch < 0 || max_new < 0 || num_q_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 ||
+        page_size <= 0 || num_q_heads % num_kv_heads != 0)
+        return -1;
+    const int G = num_q_heads / num_kv_heads, d = head_dim, T = max_new;
+    int status = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int L = seq_lens[b], n = new_lens[b];
+        if (L < 0 || n < 0 || n > T) return -1;
+    }
+    for (int b = 0; b < batch; ++b) {
+        const int L = seq_lens[b], n = new_lens[b];
+        const int32_t *pt = page_table + (int64_t)b * max_pages_per_seq;
+        int ok = 1;
+        for (int j = 0; j < L + n && ok; j += page_size) {
+            const int slot = j / page_size;
+            if (slot >= max_pages_per_seq || pt[slot] < 0 || pt[slot] >= num_pages) ok = 0;
+        }
+        if (!ok) { status = -4; continue; }
+        /* append the new tokens' K/V rows */
+        for (int i = 0; i < n; ++i) {
+            const int pos = L + i;
+            const int64_t base = (int64_t)pt[pos / page_size] * stride_page + (int64_t)(pos % page_size) * stride_tok;
+            for (int g = 0; g < num_kv_heads; ++g) {
+                const uint16_t *ks = k_new + (((int64_t)b * T + i) * num_kv_heads + g) * d;
+                const uint16_t *vs = v_new + (((int64_t)b * T + i) * num_kv_heads + g) * d;
+                memcpy(k_pool + base + (int64_t)g * stride_head, ks, sizeof(uint16_t) * (size_t)d);
+                memcpy(v_pool + base + (int64_t)g * stride_head, vs, sizeof(uint16_t) * (size_t)d);
+            }
+        }
+        /* causal attention of every new token over the cache as it now stands */
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+        for (int i = 0; i < n; ++i) {
+            for (int h = 0; h < num_q_heads; ++h) {
+                const int g = h / G, vis = L + i + 1;
+                double *s = (double *)malloc(sizeof(double) * (size_t)vis);
+                if (!s) {
+#pragma omp atomic write
+                    status = -1;
+                    continue;
+                }
+                const uint16_t *qv = q + (((int64_t)b * T + i) * num_q_heads + h) * d;
+                for (int j = 0; j < vis; ++j) {
+                    const uint16_t *kv = k_pool + (int64_t)pt[j / page_size] * stride_page + (int64_t)g * stride_head +
+                                         (int64_t)(j % page_size) * stride_tok;
+                    double acc = 0.0;
+                    for (int c = 0; c < d; ++c) acc += bf16_to_f64(qv[c]) * bf16_to_f64(kv[c]);
+                    s[j] = sm_scale * acc;
+                }
+                double mx = s[0];
+                for (int j = 1; j < vis; ++j) if (s[j] > mx) mx = s[j];
+                double denom = 0.0;
+                for (int j = 0; j < vis; ++j) { s[j] = exp(s[j] - mx); denom += s[j]; }
+                double *o = out + (((int64_t)b * T + i) * num_q_heads + h) * d;
+                for (int c = 0; c < d; ++c) o[c] = 0.0;
+                for (int j = 0; j < vis; ++j) {
+                    const uint16_t *vv = v_pool + (int64_t)pt[j / page_size] * stride_page + (int64_t)g * stride_head +
+                                         (int64_t)(j % page_size) * stride_tok;
+                    const double p = s[j] / denom;
+                    for (int c = 0; c < d; ++c) o[c] += p * bf16_to_f64(vv[c]);
+                }
+                free(s);
+            }
+        }
+        seq_lens[b] = L + n;
     }
     return status;
 }
