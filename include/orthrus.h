@@ -206,6 +206,36 @@ orthrus_status orthrus_sampling_consensus_commit(orthrus_ctx *ctx, const orthrus
                                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * AR-view prefill attention of one layer — Section 3.1 (first paragraph) and Section 3.3: the frozen AR
+ * view processes the context with its ordinary causal self-attention, and the K/V it produces is the
+ * cache both views share afterwards.  Per sequence b with L = seq_lens[b] cached tokens and
+ * n = new_lens[b] new tokens (0 <= n <= max_new_tokens; L > 0 continues an earlier prefill or decode):
+ *   rows i < n of k_new / v_new are written to token positions L+i of the pools,
+ *   out[b][i][h][:] = softmax over cache tokens j = 0 .. L+i of (sm_scale * <q[b][i][h], K_j>) applied to V_j
+ *                     (token L+i sees everything before it and itself), for i < n,
+ *   seq_lens[b] = L + n.
+ * Rows i >= n of out are not written.
+ *
+ *   max_new_tokens [host value] T: row stride of q, k_new, v_new, out along the token axis
+ *   q, out         [dev] bf16 [B, T, H_q, d]
+ *   k_new, v_new   [dev] bf16 [B, T, H_kv, d]
+ *   new_lens       [dev] int32 [B]
+ *   k_pool, v_pool [dev] bf16, updated in place; page_table [dev]; seq_lens [dev] int32 [B], updated
+ *   p->max_seq_len [host] must bound L + n of every sequence; p->block_k, p->num_splits, p->vocab unused
+ *   workspace      at least orthrus_prefill_workspace_bytes(p, T)
+ * Supported: H_q / H_kv <= 8 (and the head sizes / page sizes of orthrus_params).
+ * Device-side errors: a sequence whose lengths are out of range or whose new positions are not all
+ * mapped is left untouched (cache, length, output) and the context's error word is set
+ * (ORTHRUS_ECAPACITY).  Output within the tolerance of orthrus_dual_view_attn; cache rows bit-exact.
+ */
+int64_t orthrus_prefill_workspace_bytes(const orthrus_params *p, int32_t max_new_tokens);
+orthrus_status orthrus_prefill_attn(orthrus_ctx *ctx, const orthrus_params *p, int32_t max_new_tokens,
+                                    const void *q, const void *k_new, const void *v_new, const int32_t *new_lens,
+                                    void *k_pool, void *v_pool,
+                                    const int32_t *page_table, int32_t *seq_lens, void *out,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Replay of a fixed sequence of compute calls as one HIP graph.  A decode cycle is two passes of the
  * whole layer stack plus the consensus (Section 3.2-3.3; Section 4 counts "forward passes"), i.e. tens
  * of short launches whose arguments do not change from cycle to cycle when the caller reuses its

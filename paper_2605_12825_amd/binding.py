@@ -27,6 +27,7 @@ EXPORTED = [
     "orthrus_create", "orthrus_destroy", "orthrus_status_string", "orthrus_attn_workspace_bytes",
     "orthrus_consensus_workspace_bytes", "orthrus_sampling_workspace_bytes", "orthrus_attn_num_splits",
     "orthrus_dual_view_attn", "orthrus_consensus_commit", "orthrus_sampling_consensus_commit",
+    "orthrus_prefill_workspace_bytes", "orthrus_prefill_attn",
     "orthrus_graph_begin", "orthrus_graph_end", "orthrus_graph_launch", "orthrus_graph_destroy",
     "orthrus_attn_timing", "orthrus_attn_timing_read", "orthrus_last_device_error",
 ]
@@ -87,6 +88,11 @@ def _load() -> ctypes.CDLL:
     lib.orthrus_sampling_consensus_commit.restype = ctypes.c_int
     lib.orthrus_sampling_consensus_commit.argtypes = [vp, pp, ctypes.c_float, vp, vp, i32p, vp, vp, vp, vp, vp, vp,
                                                       i32p, i32p, i32p, i32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+    lib.orthrus_prefill_workspace_bytes.restype = ctypes.c_int64
+    lib.orthrus_prefill_workspace_bytes.argtypes = [pp, ctypes.c_int32]
+    lib.orthrus_prefill_attn.restype = ctypes.c_int
+    lib.orthrus_prefill_attn.argtypes = [vp, pp, ctypes.c_int32, vp, vp, vp, i32p, vp, vp, i32p, i32p, vp, vp,
+                                         ctypes.c_size_t, vp]
     lib.orthrus_graph_begin.restype = ctypes.c_int
     lib.orthrus_graph_begin.argtypes = [vp, vp]
     lib.orthrus_graph_end.restype = ctypes.c_int
@@ -215,6 +221,22 @@ def orthrus_sampling_consensus_commit(ctx, p: orthrus_params, temperature: float
     if check and st != ORTHRUS_OK:
         raise OrthrusError(st, "orthrus_sampling_consensus_commit")
     return st
+
+
+def orthrus_prefill_workspace_bytes(p: orthrus_params, max_new_tokens: int) -> int:
+    n = _lib.orthrus_prefill_workspace_bytes(ctypes.byref(p), int(max_new_tokens))
+    if n < 0:
+        raise OrthrusError(int(n), "orthrus_prefill_workspace_bytes")
+    return int(n)
+
+
+def orthrus_prefill_attn(ctx, p: orthrus_params, max_new_tokens: int, q, k_new, v_new, new_lens, k_pool, v_pool,
+                         page_table, seq_lens, out, workspace, stream=None) -> None:
+    st = _lib.orthrus_prefill_attn(ctx, ctypes.byref(p), int(max_new_tokens), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                   _ptr(new_lens), _ptr(k_pool), _ptr(v_pool), _ptr(page_table), _ptr(seq_lens),
+                                   _ptr(out), _ptr(workspace), _nbytes(workspace), _stream_handle(stream))
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_prefill_attn")
 
 
 def orthrus_graph_begin(ctx, stream) -> None:

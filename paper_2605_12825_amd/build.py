@@ -7,7 +7,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liborthrus.so")
-SOURCES = ["orthrus_api.hip", "orthrus_attn.hip", "orthrus_consensus.hip", "orthrus_sampling.hip"]
+SOURCES = ["orthrus_api.hip", "orthrus_attn.hip", "orthrus_consensus.hip", "orthrus_sampling.hip",
+           "orthrus_prefill.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",

@@ -199,6 +199,7 @@ orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p,
     a.part_o = (float *)workspace;
     a.part_ml = (float *)((char *)workspace + align_up(plan.part_o_bytes, 256));
     a.err_word = ctx->err_word;
+    a.old_lens = nullptr; a.new_lens = nullptr; a.max_new = 0;
     a.stride_page = p->pool_stride_page; a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok;
     a.num_pages = p->num_pages;
     a.batch = p->batch; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
@@ -232,6 +233,70 @@ orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p,
             }
         }
     }
+    return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
+int64_t orthrus_prefill_workspace_bytes(const orthrus_params *p, int32_t max_new_tokens)
+{
+    orthrus_status s = check_params(p, true, false, true);
+    if (s != ORTHRUS_OK) return (int64_t)s;
+    if (max_new_tokens < 0) return (int64_t)ORTHRUS_EINVAL;
+    return (int64_t)(2 * align_up((size_t)p->batch * sizeof(int32_t), 256));
+}
+
+orthrus_status orthrus_prefill_attn(orthrus_ctx *ctx, const orthrus_params *p, int32_t max_new_tokens,
+                                    const void *q, const void *k_new, const void *v_new, const int32_t *new_lens,
+                                    void *k_pool, void *v_pool,
+                                    const int32_t *page_table, int32_t *seq_lens, void *out,
+                                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx) return ORTHRUS_EINVAL;
+    orthrus_status s = check_params(p, true, false, true);
+    if (s != ORTHRUS_OK) return s;
+    if (max_new_tokens < 0) return ORTHRUS_EINVAL;
+    const int group = p->num_q_heads / p->num_kv_heads;
+    if (group > 8) return ORTHRUS_EUNSUPPORTED;  // 32 * group rows per work item, at most 256
+    if (!q || !k_new || !v_new || !new_lens || !k_pool || !v_pool || !page_table || !seq_lens || !out)
+        return ORTHRUS_EINVAL;
+    const uintptr_t al = (uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)k_pool | (uintptr_t)v_pool |
+                         (uintptr_t)out;
+    if (al & 15) return ORTHRUS_EINVAL;
+    if (p->batch == 0 || max_new_tokens == 0) return ORTHRUS_OK;
+    const int64_t chunks = ((int64_t)max_new_tokens + 31) / 32;
+    if (chunks * p->num_kv_heads * p->batch > 0x3fffffff) return ORTHRUS_EUNSUPPORTED;
+    const size_t o1 = align_up((size_t)p->batch * sizeof(int32_t), 256);
+    if (!workspace || workspace_bytes < 2 * o1 || ((uintptr_t)workspace & 255)) return ORTHRUS_EWORKSPACE;
+
+    orthrus::PrefillArgs f;
+    f.k_new = (const uint16_t *)k_new; f.v_new = (const uint16_t *)v_new; f.new_lens_in = new_lens;
+    f.k_pool = (uint16_t *)k_pool; f.v_pool = (uint16_t *)v_pool;
+    f.page_table = page_table; f.seq_lens = seq_lens;
+    f.old_lens = (int32_t *)workspace; f.new_lens = (int32_t *)((char *)workspace + o1);
+    f.err_word = ctx->err_word;
+    f.stride_page = p->pool_stride_page; f.stride_head = p->pool_stride_head; f.stride_tok = p->pool_stride_tok;
+    f.num_pages = p->num_pages;
+    f.batch = p->batch; f.max_new = max_new_tokens; f.num_kv_heads = p->num_kv_heads; f.head_dim = p->head_dim;
+    f.page_shift = log2_exact(p->page_size); f.max_pages_per_seq = p->max_pages_per_seq;
+    f.max_seq_len = p->max_seq_len;
+    hipError_t e = orthrus::launch_prefill_append(f, (hipStream_t)stream);
+    if (e != hipSuccess) return ORTHRUS_EHIP;
+
+    orthrus::AttnArgs a;
+    a.q = (const uint16_t *)q; a.k_blk = nullptr; a.v_blk = nullptr;
+    a.k_pool = (const uint16_t *)k_pool; a.v_pool = (const uint16_t *)v_pool;
+    a.page_table = page_table; a.seq_lens = seq_lens;
+    a.out = (uint16_t *)out; a.lse = nullptr; a.part_o = nullptr; a.part_ml = nullptr;
+    a.err_word = ctx->err_word;
+    a.old_lens = f.old_lens; a.new_lens = f.new_lens; a.max_new = max_new_tokens;
+    a.stride_page = p->pool_stride_page; a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok;
+    a.num_pages = p->num_pages;
+    a.batch = p->batch; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
+    a.group = group; a.block_k = 32; a.rows = 32 * group;
+    a.page_shift = f.page_shift; a.max_pages_per_seq = p->max_pages_per_seq;
+    a.max_seq_len = p->max_seq_len; a.chunk_tokens = 0; a.num_splits = (int)chunks;
+    a.view = (int)ORTHRUS_VIEW_AR_VERIFY;
+    a.scale_log2e = p->sm_scale * 1.4426950408889634f;
+    e = orthrus::launch_prefill_attn(a, p->head_dim, (hipStream_t)stream);
     return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
 }
 

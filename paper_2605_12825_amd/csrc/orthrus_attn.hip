@@ -119,7 +119,12 @@ struct AttnGeom {
 // wave), so when compute waves issue their own loads the two costs add up; with a dedicated loader
 // wave they overlap.  The compute waves stay below 168 registers, so W + 1 <= 9 waves fit a CU at
 // three waves per SIMD.
-template <int D, int W, int NS>
+//
+// PREFILL = 1 turns the same kernel into the AR view's causal prefill attention (Section 3.1): the new
+// tokens' K/V rows are already in the cache, a work item is (sequence, chunk of 32 new tokens, KV head),
+// its R = 32*G rows are the chunk's tokens times the G query heads, row (token i) sees cache tokens
+// 0 .. L+i (its own position included), and there is no staged block tile and no split.
+template <int D, int W, int NS, int PREFILL = 0>
 __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnArgs a)
 {
     using Gm = AttnGeom<D>;
@@ -139,7 +144,7 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
     // Workgroup id -> (sequence, split, KV head) with the sequence index fastest and the head slowest.
     // Consecutive workgroup ids go to different XCDs; a head's rows sit at a fixed offset inside every
     // page, so an order that ties XCD k to head k makes each XCD hammer its own subset of the HBM
-    // channels and the XCDs finish far apart.
+    // channels and the XCDs finish far apart.  (Prefill: the middle index is the chunk, longest first.)
     const int b = (int)(blockIdx.x % (unsigned)a.batch);
     const int split = (int)((blockIdx.x / (unsigned)a.batch) % (unsigned)a.num_splits);
     const int g = (int)(blockIdx.x / ((unsigned)a.batch * (unsigned)a.num_splits));
@@ -149,17 +154,35 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
     // Lengths and the page table are read-only for the whole launch and every index used here is
     // wave-uniform: reading them through the constant address space makes these scalar loads
     // (s_load_dword), which keeps them off the vector-memory counter that paces the tile loads.
-    int L = ((const const_i32 *)a.seq_lens)[b];
-    if (L < 0 || L > a.max_seq_len) {
-        if (tid == 0) atomicExch(a.err_word, -4);
-        L = L < 0 ? 0 : a.max_seq_len;
+    int t_begin, t_end, n_cache, n_tiles;
+    int row0 = 0, rows_live = K;  // prefill: first new-token index of the chunk, tokens in it; pos0 below
+    int pos0 = 0;                 // prefill: cache position of the chunk's first token
+    if constexpr (PREFILL) {
+        // lengths as the planning kernel left them: validated, 0 new tokens on a capacity error
+        const int L0 = __builtin_amdgcn_readfirstlane(((const const_i32 *)a.old_lens)[b]);
+        const int n_new = __builtin_amdgcn_readfirstlane(((const const_i32 *)a.new_lens)[b]);
+        const int chunk = a.num_splits - 1 - split;  // the chunks with the most cache tokens start first
+        row0 = chunk * 32;
+        if (row0 >= n_new) return;
+        rows_live = min(32, n_new - row0);
+        pos0 = L0 + row0;
+        t_begin = 0;
+        t_end = pos0 + rows_live;  // everything up to the chunk's last token
+        n_cache = (t_end + 31) >> 5;
+        n_tiles = n_cache;
+    } else {
+        int L = ((const const_i32 *)a.seq_lens)[b];
+        if (L < 0 || L > a.max_seq_len) {
+            if (tid == 0) atomicExch(a.err_word, -4);
+            L = L < 0 ? 0 : a.max_seq_len;
+        }
+        L = __builtin_amdgcn_readfirstlane(L);  // wave-uniform by construction; keeps the loop control scalar
+        t_begin = split * a.chunk_tokens;
+        if (split > 0 && t_begin >= L) return;  // nothing of this sequence falls in the split
+        t_end = min(L, t_begin + a.chunk_tokens);
+        n_cache = t_end > t_begin ? (t_end - t_begin + 31) >> 5 : 0;
+        n_tiles = n_cache + (split == 0 ? 1 : 0);  // split 0 ends with the in-block tile
     }
-    L = __builtin_amdgcn_readfirstlane(L);  // wave-uniform by construction; keeps the loop control scalar
-    const int t_begin = split * a.chunk_tokens;
-    if (split > 0 && t_begin >= L) return;  // nothing of this sequence falls in the split
-    const int t_end = min(L, t_begin + a.chunk_tokens);
-    const int n_cache = t_end > t_begin ? (t_end - t_begin + 31) >> 5 : 0;
-    const int n_tiles = n_cache + (split == 0 ? 1 : 0);  // split 0 ends with the in-block tile
     const const_i32 *pt_row = (const const_i32 *)(a.page_table + (int64_t)b * a.max_pages_per_seq);
 
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)smem;
@@ -287,10 +310,14 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
     Frag qf[KSTEPS];
     int irow;
     const int ridx = wave * 32 + col;
-    if (ridx < a.rows) {
+    // the lane's row exists: inside the R rows and, for prefill, inside the chunk's live tokens
+    const bool row_ok = ridx < a.rows && (!PREFILL || ridx / G < rows_live);
+    // row of q / out that holds block row (or new token) i of this sequence
+    const int64_t row_base = PREFILL ? (int64_t)b * a.max_new + row0 : (int64_t)b * K;
+    if (row_ok) {
         const int i = ridx / G, hl = ridx - i * G;
         irow = i;
-        const uint16_t *qp = a.q + (((int64_t)b * K + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
+        const uint16_t *qp = a.q + ((row_base + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) qf[kk].u = *(const uint4 *)(qp + kk * 16 + h * 8);
     } else {
@@ -344,6 +371,7 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
         int lim = 32;
         if (i < n_cache) lim = t_end - (t_begin + i * 32);
         else lim = a.view == 0 ? K : min(K, irow + 1);  // in-block tile: K rows, causal for the AR view
+        if constexpr (PREFILL) lim = min(lim, pos0 + irow + 1 - i * 32);  // causal: tokens up to the row's own
 
         f32x16 s;
 #pragma unroll
@@ -418,11 +446,11 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
 
     // ---- write-out: this wave's 32 rows
     l_run = sum_with_other_half(l_run);
-    if (a.num_splits == 1) {
-        if (ridx < a.rows) {
+    if (PREFILL || a.num_splits == 1) {
+        if (row_ok) {
             const int i = irow, hl = ridx - i * G;
             const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
-            uint16_t *op = a.out + (((int64_t)b * K + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
+            uint16_t *op = a.out + ((row_base + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
 #pragma unroll
             for (int db = 0; db < DBLK; ++db)
 #pragma unroll
@@ -617,6 +645,34 @@ static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStr
         e = hipGetLastError();
     }
     return e;
+}
+
+template <int D, int W>
+static hipError_t launch_prefill_variant(const AttnArgs &a, size_t lds_bytes, hipStream_t stream)
+{
+    dim3 grid((unsigned)a.num_splits * (unsigned)a.num_kv_heads * (unsigned)a.batch);
+    hipLaunchKernelGGL((attn_split_kernel<D, W, kStages, 1>), grid, dim3(64 * (W + 1)), lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+// Prefill attention: a.num_splits carries the number of 32-token chunks per sequence, a.rows = 32 * group.
+hipError_t launch_prefill_attn(const AttnArgs &a, int head_dim, hipStream_t stream)
+{
+    if (a.batch == 0 || a.num_splits == 0) return hipSuccess;
+    int W = 1;
+    while (W < a.group) W *= 2;
+    const size_t lds = lds_need(head_dim);
+    switch (head_dim * 10 + W) {
+    case 1281: return launch_prefill_variant<128, 1>(a, lds, stream);
+    case 1282: return launch_prefill_variant<128, 2>(a, lds, stream);
+    case 1284: return launch_prefill_variant<128, 4>(a, lds, stream);
+    case 1288: return launch_prefill_variant<128, 8>(a, lds, stream);
+    case 641: return launch_prefill_variant<64, 1>(a, lds, stream);
+    case 642: return launch_prefill_variant<64, 2>(a, lds, stream);
+    case 644: return launch_prefill_variant<64, 4>(a, lds, stream);
+    case 648: return launch_prefill_variant<64, 8>(a, lds, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream,

@@ -26,6 +26,9 @@ struct AttnArgs {
     float *part_o;   // [unit][split][wave][d block][4][lane] float4: unnormalised partial outputs, register order
     float *part_ml;  // [unit][split][wave][32 rows] float2: running max (log2 domain) and sum
     int32_t *err_word;
+    // prefill only: lengths before the call and validated new-token counts [B] (workspace), row stride T
+    const int32_t *old_lens, *new_lens;
+    int max_new;
     int64_t stride_page, stride_head, stride_tok, num_pages;
     int batch, num_q_heads, num_kv_heads, group, block_k, rows;
     int page_shift, max_pages_per_seq, max_seq_len, chunk_tokens, num_splits, view;
@@ -72,8 +75,24 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
                      int requested_splits, int num_cus, AttnPlan *plan);
 hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream,
                        AttnLaunchEvents *events = nullptr);
+hipError_t launch_prefill_attn(const AttnArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_consensus(const ConsensusArgs &a, hipStream_t stream);
 hipError_t launch_sampling_consensus(const SamplingArgs &a, hipStream_t stream);
 int consensus_chunk_elems();
+
+// Prefill front end (defined with the commit kernels): validates lengths and pages, records the lengths
+// before the call and the accepted new-token counts, bumps seq_lens, then copies the new K/V rows in.
+struct PrefillArgs {
+    const uint16_t *k_new, *v_new;   // [B][T][H_kv][d]
+    const int32_t *new_lens_in;      // [B] requested new tokens
+    uint16_t *k_pool, *v_pool;
+    const int32_t *page_table;
+    int32_t *seq_lens;
+    int32_t *old_lens, *new_lens;    // [B] outputs (workspace)
+    int32_t *err_word;
+    int64_t stride_page, stride_head, stride_tok, num_pages;
+    int batch, max_new, num_kv_heads, head_dim, page_shift, max_pages_per_seq, max_seq_len;
+};
+hipError_t launch_prefill_append(const PrefillArgs &a, hipStream_t stream);
 
 }  // namespace orthrus

@@ -97,6 +97,15 @@ class DecodeStep:
                                                    page_table, seq_lens, accept_len, num_committed, out_tokens,
                                                    next_anchor, self.cons_ws, stream)
 
+    def prefill(self, max_new_tokens, q, k_new, v_new, new_lens, k_pool, v_pool, page_table, seq_lens, out,
+                stream=None):
+        """AR-view prefill attention of one layer (appends the new K/V rows, causal attention over the cache)."""
+        need = B.orthrus_prefill_workspace_bytes(self.params, max_new_tokens)
+        if getattr(self, "prefill_ws", None) is None or self.prefill_ws.numel() < need:
+            self.prefill_ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        return B.orthrus_prefill_attn(self.ctx, self.params, max_new_tokens, q, k_new, v_new, new_lens, k_pool,
+                                      v_pool, page_table, seq_lens, out, self.prefill_ws, stream)
+
     def attn_timing(self, enable: bool) -> None:
         """Attach HIP events to the attention kernels of the following attn() calls (or stop doing so)."""
         B.orthrus_attn_timing(self.ctx, enable)
