@@ -51,6 +51,9 @@ def parse():
                          "through every layer, the AR pass through every layer, consensus + commit into all of them")
     ap.add_argument("--graph", action="store_true", help="replay each cycle as one HIP graph instead of eager launches")
     ap.add_argument("--block-k", type=int, default=0, help="override the workload's block size K (latency-vs-K sweeps)")
+    ap.add_argument("--prefill", type=int, default=0,
+                    help="> 0: time orthrus_prefill_attn (AR prefill of one layer) for that many new tokens per "
+                         "sequence on an empty cache, with the workload's head shapes and batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-every", type=int, default=8,
                     help="time the kernels of every Nth timed step with HIP events (0: never)")
@@ -92,6 +95,76 @@ def cpu_baseline(w, cache, host_sets, cons_sets):
             "sample": "%d whole step(s) of the same workload at the initial cache lengths: both attention views "
                       "over all %d sequences%s; mean %.2f s per step" %
                       (len(times), w.batch, " + consensus" if cons_sets else "", mean)}
+
+
+def run_prefill(args, torch, rt, w):
+    """AR prefill attention of one layer: T new tokens per sequence on an empty cache (Section 3.1)."""
+    import oracle
+    from orthrus_inputs import f32_to_bf16_bits, make_cache
+    T, B = args.prefill, w.batch
+    w = w.with_(context=0, context_range=None, steps=(T + w.block_k - 1) // w.block_k + 1)
+    cache = make_cache(w)
+    rng = np.random.default_rng(w.seed + 77)
+    mk = lambda h: f32_to_bf16_bits(rng.standard_normal((B, T, h, w.head_dim), dtype=np.float32))
+    hq, hk, hv = mk(w.num_q_heads), mk(w.num_kv_heads), mk(w.num_kv_heads)
+    D = rt.to_device_bits
+    q, kn, vn = D(hq), D(hk), D(hv)
+    k_pool, v_pool = D(cache["k_pool"]), D(cache["v_pool"])
+    page_table = D(cache["page_table"])
+    new_lens = torch.full((B,), T, dtype=torch.int32, device="cuda:0")
+    zero = torch.zeros((B,), dtype=torch.int32, device="cuda:0")
+    seq_lens = zero.clone()
+    out = torch.empty_like(q)
+    step = rt.DecodeStep(batch=B, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
+                         block_k=w.block_k, page_size=w.page_size, max_pages_per_seq=cache["page_table"].shape[1],
+                         max_seq_len=T, num_pages=cache["num_pages"])
+    stream = torch.cuda.current_stream()
+
+    def one():
+        seq_lens.copy_(zero)   # every timed call prefills the same empty cache again
+        step.prefill(T, q, kn, vn, new_lens, k_pool, v_pool, page_table, seq_lens, out)
+    for _ in range(args.warmup):
+        one()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        one()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    if step.device_error() != 0:
+        log("bench.py: device error after the timed region")
+        sys.exit(4)
+    ms = e0.elapsed_time(e1) / args.steps
+    # 2 contractions x 2 flop per multiply-add x d per (query, visible key) pair, causal: T(T+1)/2 pairs
+    flops = 4.0 * w.head_dim * w.num_q_heads * B * (T * (T + 1) / 2.0)
+    tf = flops / (ms * 1e-3) / 1e12
+    res = {
+        "metric": "AR prefill attention of one layer (causal, paged), whole call", "value": round(B * T / (ms * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s head shapes, prefill of %d tokens x %d sequences on an empty cache" % (w.name, T, B),
+                   "batch": B, "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim,
+                   "page_size": w.page_size, "new_tokens": T},
+        "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": round(tf / 2500.0, 4), "traffic": None,
+                     "kernel": "orthrus_prefill_attn = plan + append + attn_split_kernel (prefill form); ordinary "
+                               "events around the whole call, so launch gaps are inside",
+                     "avg_launch_us": round(ms * 1e3, 2), "algorithmic_flops_per_launch": int(flops)},
+    }
+    if not args.no_cpu_baseline:
+        n = min(T, 256)   # bounded sample: the first n tokens of every sequence
+        c = np.ascontiguousarray
+        t0 = time.perf_counter()
+        oracle.prefill_attn(w.sm_scale, c(hq[:, :n]), c(hk[:, :n]), c(hv[:, :n]), np.full(B, n, np.int32),
+                            cache["k_pool"].copy(), cache["v_pool"].copy(), cache["page_table"],
+                            np.zeros(B, np.int32))
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": round(B * n / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "prefill of the first %d tokens of each sequence "
+                               "(cost grows with the square of the length: not comparable beyond that)" % n}
+    step.close()
+    print(json.dumps(res), flush=True)
 
 
 def run_stack(args, torch, rt, w, cache, host_sets, cons_sets, splits):
@@ -211,6 +284,9 @@ def main():
     if args.paging:
         w = w.with_(paging=args.paging)
     splits = w.num_splits if args.num_splits < 0 else args.num_splits
+    if args.prefill > 0:
+        run_prefill(args, torch, rt, WORKLOADS[args.workload])
+        return
     t_gen = time.perf_counter()
     cache = make_cache(w)
     host_sets = []
