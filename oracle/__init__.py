@@ -236,3 +236,41 @@ def sampling_consensus_commit(ar_logits: np.ndarray, diff_logits: np.ndarray, dr
         raise RuntimeError("orthrus_oracle_sampling_consensus_commit failed with status %d" % rc)
     return dict(accept_len=accept_len, num_committed=num_committed, out_tokens=out_tokens,
                 next_anchor=next_anchor, status=rc, margin_accept=m_acc, margin_draw=m_draw)
+
+
+def block_mask_attn(sm_scale: float, block_k: int, anchors: np.ndarray, q_diff: np.ndarray,
+                    k_ar: np.ndarray, v_ar: np.ndarray, k_diff: np.ndarray, v_diff: np.ndarray) -> np.ndarray:
+    """Diffusion-view attention under the training block mask M_diff (Section 3.2, Eq. 6), evaluated literally.
+
+    The key axis is the L clean AR keys followed by the NB*K diffusion keys of all blocks.  For the diffusion
+    query at index qi (block nb = qi // K, anchor a = anchors[nb]) and key index k:
+        allowed  <=>  (k < L and k <= a - 1)  or  (k >= L and qi // K == (k - L) // K)
+    Dense scores over the whole key axis, the mask, a softmax and the weighted sum, in fp64 with numpy
+    (one query head at a time).  ``q_diff`` [NB*K,H_q,d], ``k_ar``/``v_ar`` [L,H_kv,d],
+    ``k_diff``/``v_diff`` [NB*K,H_kv,d] as bf16 bit patterns; returns fp64 [NB*K,H_q,d].
+    """
+    from orthrus_inputs import bf16_bits_to_f32
+    f = lambda a: bf16_bits_to_f32(a).astype(np.float64)
+    Q, KA, VA, KD, VD = f(q_diff), f(k_ar), f(v_ar), f(k_diff), f(v_diff)
+    NQ, Hq, d = Q.shape
+    L, Hkv, _ = KA.shape
+    K = int(block_k)
+    if NQ % K or KD.shape[0] != NQ or len(anchors) != NQ // K:
+        raise ValueError("shape mismatch")
+    G = Hq // Hkv
+    qi = np.arange(NQ)[:, None]
+    kk = np.arange(L + NQ)[None, :]
+    a_of_q = np.asarray(anchors, dtype=np.int64)[qi // K]
+    allowed = ((kk < L) & (kk <= a_of_q - 1)) | ((kk >= L) & (qi // K == (kk - L) // K))
+    out = np.empty((NQ, Hq, d), dtype=np.float64)
+    for h in range(Hq):
+        g = h // G
+        keys = np.concatenate([KA[:, g], KD[:, g]])
+        vals = np.concatenate([VA[:, g], VD[:, g]])
+        s = (Q[:, h] @ keys.T) * float(sm_scale)
+        s = np.where(allowed, s, -np.inf)
+        s = s - s.max(axis=1, keepdims=True)
+        p = np.exp(s)
+        p /= p.sum(axis=1, keepdims=True)
+        out[:, h] = p @ vals
+    return out
