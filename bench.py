@@ -54,6 +54,10 @@ def parse():
     ap.add_argument("--prefill", type=int, default=0,
                     help="> 0: time orthrus_prefill_attn (AR prefill of one layer) for that many new tokens per "
                          "sequence on an empty cache, with the workload's head shapes and batch")
+    ap.add_argument("--train-mask", type=int, default=0,
+                    help="> 0: time the diffusion view's training block-mask forward (Eq. 6) for that many packed "
+                         "sequences of 2048 tokens with 256 anchor blocks of K=32 each (the paper's training "
+                         "geometry), with the workload's head shapes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-every", type=int, default=8,
                     help="time the kernels of every Nth timed step with HIP events (0: never)")
@@ -165,6 +169,59 @@ def run_prefill(args, torch, rt, w):
                                "(cost grows with the square of the length: not comparable beyond that)" % n}
     step.close()
     print(json.dumps(res), flush=True)
+
+
+def run_train_mask(args, torch, rt, w):
+    """Forward of the diffusion view under the training block mask (Section 3.2 Eq. 6, Appendix A geometry):
+    every anchor block is one batch entry of orthrus_dual_view_attn(DIFFUSION) over the clean context before
+    its anchor; the context's K/V stay in their plain [tokens, H_kv, d] layout (described by the pool strides)."""
+    from orthrus_inputs import f32_to_bf16_bits
+    NS, L, NB, K, P = args.train_mask, 2048, 256, 32, 16
+    Hq, Hkv, d = w.num_q_heads, w.num_kv_heads, w.head_dim
+    rng = np.random.default_rng(w.seed + 99)
+    mk = lambda n, h: f32_to_bf16_bits(rng.standard_normal((n, h, d), dtype=np.float32))
+    D = rt.to_device_bits
+    anchors = np.sort(rng.integers(1, L + 1, size=(NS, NB)), axis=1).astype(np.int32)
+    pages = L // P
+    page_table = (np.arange(NS, dtype=np.int32)[:, None, None] * pages +
+                  np.arange(pages, dtype=np.int32)[None, None, :]).repeat(NB, axis=1).reshape(NS * NB, pages)
+    q = D(mk(NS * NB * K, Hq).reshape(NS * NB, K, Hq, d))
+    kd, vd = (D(mk(NS * NB * K, Hkv).reshape(NS * NB, K, Hkv, d)) for _ in range(2))
+    k_ar, v_ar = D(mk(NS * L, Hkv)), D(mk(NS * L, Hkv))
+    out = torch.empty_like(q)
+    step = rt.DecodeStep(batch=NS * NB, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d, block_k=K, page_size=P,
+                         max_pages_per_seq=pages, max_seq_len=L, num_pages=NS * pages,
+                         pool_strides=(0, P * Hkv * d, d, Hkv * d))
+    pt, sl = D(np.ascontiguousarray(page_table)), D(anchors.reshape(-1))
+    stream = torch.cuda.current_stream()
+    one = lambda: step.attn(0, q, kd, vd, k_ar, v_ar, pt, sl, out)
+    for _ in range(args.warmup):
+        one()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        one()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    if step.device_error() != 0:
+        sys.exit(4)
+    ms = e0.elapsed_time(e1) / args.steps
+    pairs = float((anchors.astype(np.int64) + K).sum()) * K           # (query, visible key) pairs per query head
+    flops = 4.0 * d * Hq * pairs
+    tf = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "diffusion-view training block-mask attention forward (Eq. 6)", "value": round(NS * L / (ms * 1e-3), 1),
+        "unit": "packed tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%d packed sequences of %d tokens, %d anchor blocks of K=%d each, %s head shapes" %
+                               (NS, L, NB, K, w.name), "num_q_heads": Hq, "num_kv_heads": Hkv, "head_dim": d,
+                   "num_splits": step.num_splits},
+        "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": round(tf / 2500.0, 4), "traffic": None,
+                     "kernel": "orthrus_dual_view_attn(DIFFUSION) with one batch entry per anchor block",
+                     "avg_launch_us": round(ms * 1e3, 2), "algorithmic_flops_per_launch": int(flops)}}), flush=True)
+    step.close()
 
 
 def run_stack(args, torch, rt, w, cache, host_sets, cons_sets, splits):
@@ -286,6 +343,9 @@ def main():
     splits = w.num_splits if args.num_splits < 0 else args.num_splits
     if args.prefill > 0:
         run_prefill(args, torch, rt, WORKLOADS[args.workload])
+        return
+    if args.train_mask > 0:
+        run_train_mask(args, torch, rt, WORKLOADS[args.workload])
         return
     t_gen = time.perf_counter()
     cache = make_cache(w)
