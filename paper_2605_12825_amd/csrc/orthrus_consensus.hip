@@ -84,22 +84,24 @@ __global__ void __launch_bounds__(256) argmax_partial_kernel(const ConsensusArgs
     // 16-byte loads need the row start aligned; rows are 4*vocab bytes apart
     const bool vec_ok = ((a.vocab & 3) == 0) && ((((uintptr_t)a.ar_logits) & 15) == 0);
     if (vec_ok) {
-        // begin is a multiple of 4 (chunk_elems is); end too since vocab is
-        for (int i = begin + tid * 4; i < end; i += 256 * 4 * 2) {
-            const float4 x = *(const float4 *)(base + i);
-            const int i2 = i + 256 * 4;
-            float4 y = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-            const bool has2 = i2 < end;
-            if (has2) y = *(const float4 *)(base + i2);
-            if (bi == 0x7fffffff) { bv = x.x; bi = i; } else take_later(x.x, i, bv, bi);
-            take_later(x.y, i + 1, bv, bi);
-            take_later(x.z, i + 2, bv, bi);
-            take_later(x.w, i + 3, bv, bi);
-            if (has2) {
-                take_later(y.x, i2, bv, bi);
-                take_later(y.y, i2 + 1, bv, bi);
-                take_later(y.z, i2 + 2, bv, bi);
-                take_later(y.w, i2 + 3, bv, bi);
+        // begin is a multiple of 4 (chunk_elems is); end too since vocab is.  All of a thread's loads of
+        // the chunk go out before the first comparison (kChunkElems / 1024 = 8 loads of 16 bytes).
+        constexpr int NL = kChunkElems / (256 * 4);
+        float4 x[NL];
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const int i = begin + (u * 256 + tid) * 4;
+            x[u] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (i < end) x[u] = *(const float4 *)(base + i);
+        }
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const int i = begin + (u * 256 + tid) * 4;
+            if (i < end) {
+                if (bi == 0x7fffffff) { bv = x[u].x; bi = i; } else take_later(x[u].x, i, bv, bi);
+                take_later(x[u].y, i + 1, bv, bi);
+                take_later(x[u].z, i + 2, bv, bi);
+                take_later(x[u].w, i + 3, bv, bi);
             }
         }
     } else {
