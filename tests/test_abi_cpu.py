@@ -59,6 +59,48 @@ def test_workspace_queries_and_split_planning():
     assert orthrus.orthrus_attn_workspace_bytes(p) >= 2 * 2 * n * 64 * (128 + 2) * 4
 
 
+def _params_for(w, max_seq_len):
+    pages = (max_seq_len + w.page_size - 1) // w.page_size + 1
+    return B.make_params(batch=w.batch, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
+                         block_k=w.block_k, page_size=w.page_size, max_pages_per_seq=pages, max_seq_len=max_seq_len,
+                         num_pages=pages * max(w.batch, 1), vocab=max(w.vocab, 1))
+
+
+def test_split_planning_aims_at_one_workgroup_per_cu():
+    """Host logic only: the cost model's choices for the workloads of the build contract (256 CUs)."""
+    from orthrus_inputs import WORKLOADS
+    got = {}
+    for name, L in (("long", 32768), ("stress", 2048 + 512), ("layer8b", 4096), ("mixed", 8192), ("tiny", 128)):
+        got[name] = orthrus.orthrus_attn_num_splits(_params_for(WORKLOADS[name], L))
+    assert got["long"] == 8            # 4 x 8 (sequence, head) units x 8 splits = 256 workgroups
+    assert got["stress"] == 1          # 512 units already: no split, no combine
+    assert got["mixed"] == 4           # 64 units x 4
+    assert 16 <= got["layer8b"] <= 32  # 8 units: as many splits as 128-token chunks allow
+    assert got["tiny"] == 1
+    # the 64 splits the long configuration names are honoured when asked for
+    p = _params_for(WORKLOADS["long"], 32768)
+    p.num_splits = 64
+    assert orthrus.orthrus_attn_num_splits(p) == 64
+    rows, d = 64, 128
+    assert orthrus.orthrus_attn_workspace_bytes(p) >= 4 * 8 * 64 * rows * (d + 2) * 4
+
+
+def test_prefill_workspace_and_argument_checks_on_the_host():
+    p = _good()
+    assert orthrus.orthrus_prefill_workspace_bytes(p, 4096) >= 2 * 4 * p.batch
+    with pytest.raises(B.OrthrusError):
+        orthrus.orthrus_prefill_workspace_bytes(p, -1)
+    lib = ctypes.CDLL(orthrus.library_path())
+    lib.orthrus_prefill_attn.restype = ctypes.c_int
+    # null context is refused before anything else is looked at
+    assert lib.orthrus_prefill_attn(None, ctypes.byref(p), 16, None, None, None, None, None, None, None, None, None,
+                                    None, ctypes.c_size_t(0), None) == B.ORTHRUS_EINVAL
+    assert lib.orthrus_graph_begin(None, None) == B.ORTHRUS_EINVAL
+    assert lib.orthrus_graph_launch(None, None) == B.ORTHRUS_EINVAL
+    assert lib.orthrus_graph_destroy(None) == B.ORTHRUS_EINVAL
+    assert lib.orthrus_attn_timing(None, 1) == B.ORTHRUS_EINVAL
+
+
 @pytest.mark.parametrize("field,value,status", [
     ("batch", -1, B.ORTHRUS_EINVAL),
     ("num_q_heads", 7, B.ORTHRUS_EINVAL),          # not a multiple of num_kv_heads
