@@ -12,7 +12,11 @@
  *     hipStream_t passed as void*; NULL = the default stream), do not synchronise with the
  *     host and do not allocate.  Sequence lengths live on the device and are read by the
  *     kernels, so consecutive decode steps can be queued without a host round trip.
- *   - The context holds one device error word shared by every call made with it.
+ *     (While per-kernel timing is enabled an attention call creates or reuses HIP events on the host;
+ *     that is the one exception to "does not allocate", see orthrus_attn_timing.)
+ *   - The context holds one device error word shared by every call made with it, and the host-side
+ *     list of timing events.  A context is not thread-safe: calls that share one must not overlap in
+ *     time on the host; use one context per host thread.
  *   - Every function returns an orthrus_status.  Argument errors are found on the host before
  *     anything is launched; on such an error nothing has been written.
  *   - Layouts are row-major with the last index contiguous.  bf16 means the upper 16 bits of
@@ -267,7 +271,8 @@ orthrus_status orthrus_graph_destroy(orthrus_graph *graph);
  * kernels.  Events are created on first use and recycled (host-side allocation only; do not enable
  * under stream capture).  orthrus_attn_timing_read waits for the recorded kernels to finish, returns
  * the sums of kernel times in microseconds and the launch counts accumulated since the last read
- * (all [host] pointers), and resets them.
+ * (all [host] pointers), and resets them.  Events stay queued in the context until they are read: read
+ * after a bounded number of timed calls.
  */
 orthrus_status orthrus_attn_timing(orthrus_ctx *ctx, int enable);
 orthrus_status orthrus_attn_timing_read(orthrus_ctx *ctx, double *split_us, int64_t *split_launches,

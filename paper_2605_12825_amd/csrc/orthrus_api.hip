@@ -211,15 +211,24 @@ orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p,
     orthrus::AttnLaunchEvents ev;
     if (ctx->timing) {
         ev.on = true;
-        for (int k = 0; k < 2; ++k) {
+        bool ok = true;
+        for (int k = 0; k < 2 && ok; ++k) {
             for (hipEvent_t *slot : {&ev.start[k], &ev.stop[k]}) {
                 if (!ctx->free_events.empty()) {
                     *slot = ctx->free_events.back();
                     ctx->free_events.pop_back();
                 } else if (hipEventCreate(slot) != hipSuccess) {
-                    return ORTHRUS_EHIP;
+                    *slot = nullptr;
+                    ok = false;
+                    break;
                 }
             }
+        }
+        if (!ok) {  // hand back what was taken; nothing has been launched
+            for (int k = 0; k < 2; ++k)
+                for (hipEvent_t e2 : {ev.start[k], ev.stop[k]})
+                    if (e2) ctx->free_events.push_back(e2);
+            return ORTHRUS_EHIP;
         }
     }
     hipError_t e = orthrus::launch_attn(a, plan, p->head_dim, (hipStream_t)stream, &ev);
