@@ -40,32 +40,38 @@ __global__ void __launch_bounds__(256) lse_partial_kernel(const SamplingArgs a)
     constexpr int PER = kSChunk / 256;  // 32 values per thread and row
     float xp[PER], xq[PER];
     const bool vec_ok = ((V & 3) == 0) && (((((uintptr_t)a.c.ar_logits) | ((uintptr_t)a.diff_logits)) & 15) == 0);
-    float mp = -INFINITY, mq = -INFINITY;
     if (vec_ok) {
 #pragma unroll
         for (int u = 0; u < PER / 4; ++u) {
             const int i = begin + (u * 256 + tid) * 4;
             float4 vp = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY), vq = vp;
             if (i < end) { vp = *(const float4 *)(pr + i); vq = *(const float4 *)(qr + i); }
-            xp[4 * u] = vp.x * it; xp[4 * u + 1] = vp.y * it; xp[4 * u + 2] = vp.z * it; xp[4 * u + 3] = vp.w * it;
-            xq[4 * u] = vq.x * it; xq[4 * u + 1] = vq.y * it; xq[4 * u + 2] = vq.z * it; xq[4 * u + 3] = vq.w * it;
+            xp[4 * u] = vp.x; xp[4 * u + 1] = vp.y; xp[4 * u + 2] = vp.z; xp[4 * u + 3] = vp.w;
+            xq[4 * u] = vq.x; xq[4 * u + 1] = vq.y; xq[4 * u + 2] = vq.z; xq[4 * u + 3] = vq.w;
         }
     } else {
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
             const int i = begin + u * 256 + tid;
-            xp[u] = i < end ? pr[i] * it : -INFINITY;
-            xq[u] = i < end ? qr[i] * it : -INFINITY;
+            xp[u] = i < end ? pr[i] : -INFINITY;
+            xq[u] = i < end ? qr[i] : -INFINITY;
         }
     }
+    // Per thread: maximum of the raw logits (1/T > 0 keeps the order), then the sum of
+    // exp((x - max) / T) as exp2 of one fused multiply-add per element.  Entries past the end are
+    // -inf and add exp2(-inf) = 0; a thread that saw nothing but -inf keeps (max, sum) = (-inf, 0).
+    float rp = -INFINITY, rq = -INFINITY;
 #pragma unroll
-    for (int u = 0; u < PER; ++u) { mp = fmaxf(mp, xp[u]); mq = fmaxf(mq, xq[u]); }
+    for (int u = 0; u < PER; ++u) { rp = fmaxf(rp, xp[u]); rq = fmaxf(rq, xq[u]); }
+    const float c2 = it * 1.4426950408889634f;  // log2(e) / T
+    const float bp = rp == -INFINITY ? 0.f : -rp * c2, bq = rq == -INFINITY ? 0.f : -rq * c2;
     float sp = 0.f, sq = 0.f;
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-        sp += (xp[u] == -INFINITY) ? 0.f : expf(xp[u] - mp);
-        sq += (xq[u] == -INFINITY) ? 0.f : expf(xq[u] - mq);
+        sp += __builtin_amdgcn_exp2f(__builtin_fmaf(xp[u], c2, bp));
+        sq += __builtin_amdgcn_exp2f(__builtin_fmaf(xq[u], c2, bq));
     }
+    float mp = rp * it, mq = rq * it;  // maxima of the scaled logits (natural-log domain from here on)
     // wavefront, then workgroup merge in a fixed order
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -93,10 +99,17 @@ __device__ __forceinline__ int first_rejected(const SamplingArgs &a, int b, int 
     if (lane < K) {
         const int64_t row = (int64_t)b * K + lane;
         float4 r = a.lse_part[row * chunks];
-        for (int ch = 1; ch < chunks; ++ch) {
-            const float4 t = a.lse_part[row * chunks + ch];
-            lse_merge(r.x, r.y, t.x, t.y);
-            lse_merge(r.z, r.w, t.z, t.w);
+        // the row's chunk pairs, eight loads in flight at a time, merged in chunk order
+        for (int c0 = 1; c0 < chunks; c0 += 8) {
+            float4 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = a.lse_part[row * chunks + min(c0 + u, chunks - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (c0 + u < chunks) {
+                    lse_merge(r.x, r.y, t[u].x, t[u].y);
+                    lse_merge(r.z, r.w, t[u].z, t[u].w);
+                }
         }
         lsep = r.x + logf(r.y);
         lseq = r.z + logf(r.w);
@@ -142,9 +155,8 @@ __global__ void __launch_bounds__(256) draw_partial_kernel(const SamplingArgs a)
     const int begin = chunk * kSChunk, end = min(V, begin + kSChunk);
     float bp = -INFINITY, ba = -INFINITY;   // best among p > q, best of log p + g
     int ip = 0x7fffffff, ia = 0x7fffffff;
-    for (int i = begin + tid; i < end; i += 256) {
-        const float lp = pr[i] * it - lsep, lq = qr[i] * it - lseq;
-        const float g = gr[i];
+    auto visit = [&](int i, float xp, float xq, float g) __attribute__((always_inline)) {
+        const float lp = xp * it - lsep, lq = xq * it - lseq;
         const float r = expf(lp) - expf(lq);
         if (r > 0.f) {
             const float sc = logf(r) + g;
@@ -152,6 +164,35 @@ __global__ void __launch_bounds__(256) draw_partial_kernel(const SamplingArgs a)
         }
         const float sa = lp + g;
         if (better_score(sa, i, ba, ia)) { ba = sa; ia = i; }
+    };
+    const bool vec_ok = ((V & 3) == 0) &&
+                        (((((uintptr_t)a.c.ar_logits) | ((uintptr_t)a.diff_logits) | ((uintptr_t)a.gumbel)) & 15) == 0);
+    if (vec_ok) {
+        // all of a thread's loads of the chunk go out before the first score is formed
+        constexpr int NL = kSChunk / (256 * 4);
+        float4 vp[NL], vq[NL], vg[NL];
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const int i = begin + (u * 256 + tid) * 4;
+            vp[u] = vq[u] = vg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < end) {
+                vp[u] = *(const float4 *)(pr + i);
+                vq[u] = *(const float4 *)(qr + i);
+                vg[u] = *(const float4 *)(gr + i);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const int i = begin + (u * 256 + tid) * 4;
+            if (i < end) {  // indices ascend within a thread, as in the scalar loop
+                visit(i, vp[u].x, vq[u].x, vg[u].x);
+                visit(i + 1, vp[u].y, vq[u].y, vg[u].y);
+                visit(i + 2, vp[u].z, vq[u].z, vg[u].z);
+                visit(i + 3, vp[u].w, vq[u].w, vg[u].w);
+            }
+        }
+    } else {
+        for (int i = begin + tid; i < end; i += 256) visit(i, pr[i], qr[i], gr[i]);
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -206,10 +247,17 @@ __global__ void __launch_bounds__(256) sample_commit_kernel(const SamplingArgs a
         if (j < K) {
             float bp = -INFINITY, ba = -INFINITY;
             int ip = 0x7fffffff, ia = 0x7fffffff;
-            for (int ch = 0; ch < chunks; ++ch) {  // every lane walks the chunks in order: same result in all lanes
-                const float4 t = a.draw_part[(int64_t)b * chunks + ch];
-                if (better_score(t.x, __float_as_int(t.y), bp, ip)) { bp = t.x; ip = __float_as_int(t.y); }
-                if (better_score(t.z, __float_as_int(t.w), ba, ia)) { ba = t.z; ia = __float_as_int(t.w); }
+            // every lane walks the chunks in order (same result in all lanes), eight loads in flight at a time
+            for (int c0 = 0; c0 < chunks; c0 += 8) {
+                float4 t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = a.draw_part[(int64_t)b * chunks + min(c0 + u, chunks - 1)];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (c0 + u < chunks) {
+                        if (better_score(t[u].x, __float_as_int(t[u].y), bp, ip)) { bp = t[u].x; ip = __float_as_int(t[u].y); }
+                        if (better_score(t[u].z, __float_as_int(t[u].w), ba, ia)) { ba = t[u].z; ia = __float_as_int(t[u].w); }
+                    }
             }
             repl = ip != 0x7fffffff ? ip : ia;
         }
