@@ -42,7 +42,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="long")
-    ap.add_argument("--num-splits", type=int, default=-1, help="-1: the workload's setting; 0: library chooses")
+    ap.add_argument("--num-splits", default="workload",
+                    help="workload: the workload's setting; 0: library chooses; N: fixed splits; "
+                         "balanced: even partition of the batch's tiles over the resident workgroups")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="0: greedy consensus (Eq. 8); > 0: lossless sampling consensus at that temperature")
     ap.add_argument("--paging", default="", help="override the workload's page-table layout: contiguous|shuffled|scattered")
@@ -340,7 +342,9 @@ def main():
     w = w.with_(steps=(total_steps + 1) if w.vocab else 0)
     if args.paging:
         w = w.with_(paging=args.paging)
-    splits = w.num_splits if args.num_splits < 0 else args.num_splits
+    splits = {"workload": w.num_splits, "balanced": -1}.get(args.num_splits)
+    if splits is None:
+        splits = int(args.num_splits)
     if args.prefill > 0:
         run_prefill(args, torch, rt, WORKLOADS[args.workload])
         return

@@ -51,6 +51,18 @@ typedef enum {
 } orthrus_view;
 
 /*
+ * num_splits value that asks for the balanced partition.  A fixed split count cuts every
+ * sequence at the same token positions, sized by the host bound max_seq_len: when the lengths
+ * of a batch differ widely (the host cannot see them), most workgroups end early and the call
+ * lasts as long as the longest sequence's pieces.  The balanced partition instead reads the
+ * lengths on the device and gives every resident workgroup the same number of 32-token tiles,
+ * cutting sequences wherever the shares end; results are merged exactly as with fixed splits
+ * and are equally deterministic.  Meant for batches with ragged lengths; with equal lengths a
+ * fixed split count is as fast or faster.
+ */
+#define ORTHRUS_SPLITS_BALANCED (-1)
+
+/*
  * Problem description shared by all entry points (plain data, filled by the caller).
  *
  * Supported by the kernels: head_dim in {64, 128}; page_size a power of two >= 16;
@@ -68,7 +80,8 @@ typedef struct {
     int32_t page_size;         /* P: tokens per cache page */
     int32_t max_pages_per_seq; /* row length of page_table */
     int32_t max_seq_len;       /* HOST upper bound on every seq_lens[b] during the call (sizes the grid) */
-    int32_t num_splits;        /* attention: KV splits per (sequence, KV head); 0 = library chooses */
+    int32_t num_splits;        /* attention: KV splits per (sequence, KV head); 0 = library chooses;
+                                  ORTHRUS_SPLITS_BALANCED = even partition of the whole batch (below) */
     int32_t num_layers;        /* commit: layers written per call (block K/V and pools carry a layer axis) */
     int32_t vocab;             /* consensus: V */
     float sm_scale;            /* score scale of Eq. 4, normally 1/sqrt(d) */
@@ -97,7 +110,8 @@ const char *orthrus_status_string(orthrus_status s);
 int64_t orthrus_attn_workspace_bytes(const orthrus_params *p);
 int64_t orthrus_consensus_workspace_bytes(const orthrus_params *p);
 int64_t orthrus_sampling_workspace_bytes(const orthrus_params *p);
-/* Number of KV splits the attention call will use for these params (>= 1), or a negative status. */
+/* Number of KV splits the attention call will use for these params (>= 1; 0 for the balanced
+   partition, which has no fixed split count), or a negative status. */
 int32_t orthrus_attn_num_splits(const orthrus_params *p);
 
 /*

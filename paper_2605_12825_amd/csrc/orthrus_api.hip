@@ -63,7 +63,7 @@ orthrus_status check_params(const orthrus_params *p, bool need_attn, bool need_c
     if (p->block_k > 32) return ORTHRUS_EUNSUPPORTED;
     if (need_attn) {
         if (p->num_q_heads <= 0 || p->num_q_heads % p->num_kv_heads != 0) return ORTHRUS_EINVAL;
-        if (p->max_seq_len < 0 || p->num_splits < 0) return ORTHRUS_EINVAL;
+        if (p->max_seq_len < 0 || p->num_splits < ORTHRUS_SPLITS_BALANCED) return ORTHRUS_EINVAL;
         if ((int64_t)p->max_seq_len > (int64_t)p->max_pages_per_seq * p->page_size) return ORTHRUS_EINVAL;
         if (!(p->sm_scale > 0.f) || !std::isfinite(p->sm_scale)) return ORTHRUS_EINVAL;
         if ((int64_t)(p->num_q_heads / p->num_kv_heads) * p->block_k > 256) return ORTHRUS_EUNSUPPORTED;
@@ -79,6 +79,8 @@ orthrus_status make_plan(const orthrus_params *p, int num_cus, orthrus::AttnPlan
     orthrus::plan_attn(p->head_dim, p->num_q_heads / p->num_kv_heads, p->block_k, p->batch, p->num_kv_heads,
                        p->max_seq_len, p->num_splits, num_cus, plan);
     if (plan->num_splits > 65535 * 16) return ORTHRUS_EUNSUPPORTED;
+    // the balanced partition counts one head's tiles in a 32-bit int
+    if (plan->bal_wgs > 0 && (int64_t)p->batch * (p->max_seq_len / 32 + 2) > 0x7fffffff) return ORTHRUS_EUNSUPPORTED;
     return ORTHRUS_OK;
 }
 
@@ -145,7 +147,7 @@ int32_t orthrus_attn_num_splits(const orthrus_params *p)
     orthrus::AttnPlan plan;
     s = make_plan(p, kDefaultCUs, &plan);
     if (s != ORTHRUS_OK) return (int32_t)s;
-    return plan.num_splits;
+    return plan.bal_wgs > 0 ? 0 : plan.num_splits;
 }
 
 int64_t orthrus_attn_workspace_bytes(const orthrus_params *p)
@@ -206,6 +208,7 @@ orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p,
     a.group = p->num_q_heads / p->num_kv_heads; a.block_k = p->block_k; a.rows = plan.rows;
     a.page_shift = log2_exact(p->page_size); a.max_pages_per_seq = p->max_pages_per_seq;
     a.max_seq_len = p->max_seq_len; a.chunk_tokens = plan.chunk_tokens; a.num_splits = plan.num_splits;
+    a.bal_wgs = plan.bal_wgs;
     a.view = (int)view;
     a.scale_log2e = p->sm_scale * 1.4426950408889634f;
     orthrus::AttnLaunchEvents ev;
@@ -303,6 +306,7 @@ orthrus_status orthrus_prefill_attn(orthrus_ctx *ctx, const orthrus_params *p, i
     a.group = group; a.block_k = 32; a.rows = 32 * group;
     a.page_shift = f.page_shift; a.max_pages_per_seq = p->max_pages_per_seq;
     a.max_seq_len = p->max_seq_len; a.chunk_tokens = 0; a.num_splits = (int)chunks;
+    a.bal_wgs = 0;
     a.view = (int)ORTHRUS_VIEW_AR_VERIFY;
     a.scale_log2e = p->sm_scale * 1.4426950408889634f;
     e = orthrus::launch_prefill_attn(a, p->head_dim, (hipStream_t)stream);

@@ -8,7 +8,7 @@
 //            query rows that share that KV head (G query heads x K block rows).
 //            Workgroups are numbered with the sequence index fastest and the KV head slowest
 //            (consecutive ids go to different XCDs; see the kernel).
-//   waves  = W compute waves per workgroup, one per block of 32 query rows (W = 1, 2, 4 or 8), plus
+//   waves  = W compute waves per workgroup, one per block of 32 query rows (W = 1 .. 8), plus
 //            one loader wave.  Every compute wave reads every K/V tile, so the tile stream is shared:
 //            the loader sends 32-token tiles from global memory straight into an NS-stage LDS ring
 //            (global_load_lds_dwordx4: coalesced 16-byte loads, one 256-byte row per 16 lanes), NS-1
@@ -124,9 +124,20 @@ struct AttnGeom {
 // tokens' K/V rows are already in the cache, a work item is (sequence, chunk of 32 new tokens, KV head),
 // its R = 32*G rows are the chunk's tokens times the G query heads, row (token i) sees cache tokens
 // 0 .. L+i (its own position included), and there is no staged block tile and no split.
-template <int D, int W, int NS, int PREFILL = 0>
+//
+// BALANCED = 1 (decode only) replaces the fixed (sequence, split, head) grid by an even partition of
+// the whole launch's tile sequence: the tiles of all (head, sequence) units, cache tiles then the
+// in-block tile, are laid end to end (head-major), and workgroup w of the N launched takes tiles
+// [w*T/N, (w+1)*T/N).  A workgroup's range is cut into segments at unit boundaries; a segment that
+// covers its whole unit writes final rows, any other writes a partial (slot 2w when it starts inside
+// the unit, 2w+1 when it starts at the unit's first tile: a range holds at most one of each), which
+// attn_combine_kernel finds again from the same arithmetic.  With ragged lengths every workgroup
+// still gets the same number of tiles, and with N = resident workgroups nothing queues behind
+// the dispatcher.  Each segment runs the pipeline from empty (fill, loop, drain).
+template <int D, int W, int NS, int PREFILL = 0, int BALANCED = 0>
 __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnArgs a)
 {
+    static_assert(!(PREFILL && BALANCED), "the balanced partition is a decode mode");
     using Gm = AttnGeom<D>;
     constexpr int CH = Gm::CH, ROWB = Gm::ROWB, RPI = Gm::RPI, NI = Gm::NI, GS = Gm::GS;
     constexpr int TILE_B = Gm::TILE_B, STAGE_B = Gm::STAGE_B, KSTEPS = Gm::KSTEPS, DBLK = Gm::DBLK;
@@ -141,49 +152,142 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool loader = wave == W;
     const int col = lane & 31, h = lane >> 5;
-    // Workgroup id -> (sequence, split, KV head) with the sequence index fastest and the head slowest.
-    // Consecutive workgroup ids go to different XCDs; a head's rows sit at a fixed offset inside every
-    // page, so an order that ties XCD k to head k makes each XCD hammer its own subset of the HBM
-    // channels and the XCDs finish far apart.  (Prefill: the middle index is the chunk, longest first.)
-    const int b = (int)(blockIdx.x % (unsigned)a.batch);
-    const int split = (int)((blockIdx.x / (unsigned)a.batch) % (unsigned)a.num_splits);
-    const int g = (int)(blockIdx.x / ((unsigned)a.batch * (unsigned)a.num_splits));
     const int K = a.block_k, G = a.group;
     const int P = 1 << a.page_shift;
 
+    // The work item (balanced mode: the current segment) as every wave of the workgroup sees it.
     // Lengths and the page table are read-only for the whole launch and every index used here is
     // wave-uniform: reading them through the constant address space makes these scalar loads
     // (s_load_dword), which keeps them off the vector-memory counter that paces the tile loads.
-    int t_begin, t_end, n_cache, n_tiles;
+    int b, g;
+    int t_begin, t_end, n_cache, n_tiles;  // cache tokens [t_begin, t_end) in n_cache tiles; n_tiles adds the in-block tile
+    bool final_out;                        // this item holds every tile of its unit: write finished rows
+    size_t part_slot = 0;                  // else: index of the partial it writes
     int row0 = 0, rows_live = K;  // prefill: first new-token index of the chunk, tokens in it; pos0 below
     int pos0 = 0;                 // prefill: cache position of the chunk's first token
-    if constexpr (PREFILL) {
-        // lengths as the planning kernel left them: validated, 0 new tokens on a capacity error
-        const int L0 = __builtin_amdgcn_readfirstlane(((const const_i32 *)a.old_lens)[b]);
-        const int n_new = __builtin_amdgcn_readfirstlane(((const const_i32 *)a.new_lens)[b]);
-        const int chunk = a.num_splits - 1 - split;  // the chunks with the most cache tokens start first
-        row0 = chunk * 32;
-        if (row0 >= n_new) return;
-        rows_live = min(32, n_new - row0);
-        pos0 = L0 + row0;
-        t_begin = 0;
-        t_end = pos0 + rows_live;  // everything up to the chunk's last token
-        n_cache = (t_end + 31) >> 5;
-        n_tiles = n_cache;
-    } else {
-        int L = ((const const_i32 *)a.seq_lens)[b];
+    const const_i32 *pt_row;
+    int64_t head_off;
+
+    // validated length of sequence x (scalar)
+    auto seq_len = [&](int x) __attribute__((always_inline)) {
+        int L = ((const const_i32 *)a.seq_lens)[x];
         if (L < 0 || L > a.max_seq_len) {
             if (tid == 0) atomicExch(a.err_word, -4);
             L = L < 0 ? 0 : a.max_seq_len;
         }
-        L = __builtin_amdgcn_readfirstlane(L);  // wave-uniform by construction; keeps the loop control scalar
-        t_begin = split * a.chunk_tokens;
-        if (split > 0 && t_begin >= L) return;  // nothing of this sequence falls in the split
-        t_end = min(L, t_begin + a.chunk_tokens);
-        n_cache = t_end > t_begin ? (t_end - t_begin + 31) >> 5 : 0;
-        n_tiles = n_cache + (split == 0 ? 1 : 0);  // split 0 ends with the in-block tile
+        return __builtin_amdgcn_readfirstlane(L);  // wave-uniform by construction; keeps the loop control scalar
+    };
+
+    // balanced mode: position in the launch's tile sequence
+    int bal_b = 0, bal_g = 0, bal_o = 0, bal_left = 0;
+    if constexpr (BALANCED) {
+        // tiles of sequence x as a lane sees it (cache tiles + the in-block tile), 0 past the batch
+        auto lane_tiles = [&](int x) __attribute__((always_inline)) {
+            if (x >= a.batch) return 0;
+            int L = a.seq_lens[x];
+            L = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
+            return ((L + 31) >> 5) + 1;
+        };
+        int per_head = 0;  // tiles of one head's units
+        for (int x0 = 0; x0 < a.batch; x0 += 64) {
+            int n = lane_tiles(x0 + lane);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) n += __shfl_xor(n, off);
+            per_head += n;
+        }
+        per_head = __builtin_amdgcn_readfirstlane(per_head);
+        const int64_t total = (int64_t)per_head * a.num_kv_heads;
+        const int64_t nwg = total < (int64_t)gridDim.x ? total : (int64_t)gridDim.x;
+        if ((int64_t)blockIdx.x >= nwg) return;
+        const int64_t c0 = (int64_t)blockIdx.x * total / nwg, c1 = ((int64_t)blockIdx.x + 1) * total / nwg;
+        bal_left = (int)(c1 - c0);
+        bal_g = (int)(c0 / per_head);
+        const int r = (int)(c0 - (int64_t)bal_g * per_head);
+        // the sequence whose tiles contain offset r of the head: inclusive scan over 64 sequences at a time
+        int base = 0;
+        for (int x0 = 0; x0 < a.batch; x0 += 64) {
+            const int n = lane_tiles(x0 + lane);
+            int incl = n;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            const bool hit = n > 0 && base + incl - n <= r && r < base + incl;
+            const uint64_t mask = __ballot(hit);
+            if (mask) {
+                const int src = __builtin_ctzll(mask);
+                bal_b = x0 + src;
+                bal_o = r - (base + __shfl(incl - n, src));
+                break;
+            }
+            base += __shfl(incl, 63);
+        }
+        bal_b = __builtin_amdgcn_readfirstlane(bal_b);
+        bal_o = __builtin_amdgcn_readfirstlane(bal_o);
     }
-    const const_i32 *pt_row = (const const_i32 *)(a.page_table + (int64_t)b * a.max_pages_per_seq);
+
+    // Opens the next work item; false when the workgroup has none (left).
+    auto open_item = [&]() __attribute__((always_inline)) -> bool {
+        if constexpr (BALANCED) {
+            if (bal_left <= 0) return false;
+            b = bal_b;
+            g = bal_g;
+            const int L = seq_len(b);
+            const int nc = (L + 31) >> 5;                    // cache tiles of the unit; the in-block tile is tile nc
+            const int take = min(nc + 1 - bal_o, bal_left);  // tiles of this segment
+            const bool has_blk = bal_o + take == nc + 1;
+            n_tiles = take;
+            n_cache = has_blk ? take - 1 : take;
+            t_begin = bal_o * 32;
+            t_end = min(L, t_begin + n_cache * 32);
+            final_out = bal_o == 0 && has_blk;
+            part_slot = (size_t)blockIdx.x * 2 + (bal_o == 0 ? 1 : 0);
+            bal_left -= take;
+            bal_o = 0;
+            if (++bal_b == a.batch) {
+                bal_b = 0;
+                ++bal_g;
+            }
+        } else {
+            // Workgroup id -> (sequence, split, KV head) with the sequence index fastest and the head
+            // slowest.  Consecutive workgroup ids go to different XCDs; a head's rows sit at a fixed
+            // offset inside every page, so an order that ties XCD k to head k makes each XCD hammer its
+            // own subset of the HBM channels and the XCDs finish far apart.  (Prefill: the middle index
+            // is the chunk, longest first.)
+            b = (int)(blockIdx.x % (unsigned)a.batch);
+            const int split = (int)((blockIdx.x / (unsigned)a.batch) % (unsigned)a.num_splits);
+            g = (int)(blockIdx.x / ((unsigned)a.batch * (unsigned)a.num_splits));
+            if constexpr (PREFILL) {
+                // lengths as the planning kernel left them: validated, 0 new tokens on a capacity error
+                const int L0 = __builtin_amdgcn_readfirstlane(((const const_i32 *)a.old_lens)[b]);
+                const int n_new = __builtin_amdgcn_readfirstlane(((const const_i32 *)a.new_lens)[b]);
+                const int chunk = a.num_splits - 1 - split;  // the chunks with the most cache tokens start first
+                row0 = chunk * 32;
+                if (row0 >= n_new) return false;
+                rows_live = min(32, n_new - row0);
+                pos0 = L0 + row0;
+                t_begin = 0;
+                t_end = pos0 + rows_live;  // everything up to the chunk's last token
+                n_cache = (t_end + 31) >> 5;
+                n_tiles = n_cache;
+                final_out = true;
+            } else {
+                const int L = seq_len(b);
+                t_begin = split * a.chunk_tokens;
+                if (split > 0 && t_begin >= L) return false;  // nothing of this sequence falls in the split
+                t_end = min(L, t_begin + a.chunk_tokens);
+                n_cache = t_end > t_begin ? (t_end - t_begin + 31) >> 5 : 0;
+                n_tiles = n_cache + (split == 0 ? 1 : 0);  // split 0 ends with the in-block tile
+                final_out = a.num_splits == 1;
+                part_slot = ((size_t)b * a.num_kv_heads + g) * a.num_splits + split;
+            }
+        }
+        pt_row = (const const_i32 *)(a.page_table + (int64_t)b * a.max_pages_per_seq);
+        head_off = (int64_t)g * a.stride_head;
+        return true;
+    };
+    if (!open_item()) return;
 
     const uint32_t smem_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)smem;
     const int ld_tok = lane / CH, ld_ch = lane % CH;  // this lane's (row, slot) inside one wave-wide load
@@ -227,7 +331,6 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
     // data, masked later): nothing is fetched through an unmapped page and no LDS row is left
     // undefined; that tile and the in-block tile compute an address per lane.
     const uint32_t lane_off = (uint32_t)(ld_tok * (int)a.stride_tok + ((ld_ch ^ xm<CH>(ld_tok)) << 3)) * 2u;
-    const int64_t head_off = (int64_t)g * a.stride_head;
     auto issue_tile = [&](int t, int p0, int p1) __attribute__((always_inline)) {
         const uint32_t dst = smem_lds + (t % NS) * STAGE_B;
         if (t < n_cache) {
@@ -300,41 +403,16 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
 
     if (loader) {
         // the loader wave: nothing but the load pipeline; its last wait leaves no load outstanding
-        pipeline_fill();
-        for (int i = 0; i < n_tiles; ++i) pipeline_step(i);
+        for (;;) {
+            pipeline_fill();
+            for (int i = 0; i < n_tiles; ++i) pipeline_step(i);
+            if (!BALANCED || !open_item()) break;
+            wg_barrier();  // every compute wave is done with the previous segment's last tile
+        }
         return;
     }
 
-    // ---- compute waves.  Queries: B operand of S^T = K.Q^T, lane holds row `col` of this wave's block,
-    // d = 16*kk + 8*h .. +7 (fetched while the loader's first tiles are in flight)
-    Frag qf[KSTEPS];
-    int irow;
-    const int ridx = wave * 32 + col;
-    // the lane's row exists: inside the R rows and, for prefill, inside the chunk's live tokens
-    const bool row_ok = ridx < a.rows && (!PREFILL || ridx / G < rows_live);
-    // row of q / out that holds block row (or new token) i of this sequence
-    const int64_t row_base = PREFILL ? (int64_t)b * a.max_new + row0 : (int64_t)b * K;
-    if (row_ok) {
-        const int i = ridx / G, hl = ridx - i * G;
-        irow = i;
-        const uint16_t *qp = a.q + ((row_base + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) qf[kk].u = *(const uint4 *)(qp + kk * 16 + h * 8);
-    } else {
-        irow = 31;  // padding rows see every in-block key; their output is never stored
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) qf[kk].u = make_uint4(0, 0, 0, 0);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the queries are in registers before the loop starts
-
-    f32x16 o[DBLK];
-#pragma unroll
-    for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float m_run = kNegBig, l_run = 0.f;
-    const float c = a.scale_log2e;
-
+    // ---- compute waves
     // lane-invariant LDS read offsets inside one stage
     int kb[KSTEPS / 2];  // K operand: row `col`, chunks 4q'..4q'+3 where q' = q ^ (xm >> 2)
     {
@@ -354,128 +432,161 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
                      ((lane & 1) << 3);
     }
 
-    // ---- main loop: one barrier per tile
-    int stage = 0;  // ring slot of tile i (= i % NS)
-    for (int i = 0; i < n_tiles; ++i) {
-        wg_barrier();
-
-        // LDS addresses of this tile's operands: one add per base, the rest are instruction offsets
-        const uint32_t st_addr = smem_lds + (uint32_t)stage * STAGE_B;
-        stage = stage + 1 == NS ? 0 : stage + 1;
-        uint32_t ka[KSTEPS / 2], va_[DBLK];
-#pragma unroll
-        for (int q = 0; q < KSTEPS / 2; ++q) ka[q] = st_addr + kb[q];
-#pragma unroll
-        for (int db = 0; db < DBLK; ++db) va_[db] = st_addr + vb[db];
-        // lim = number of leading tile tokens this lane's row may see
-        int lim = 32;
-        if (i < n_cache) lim = t_end - (t_begin + i * 32);
-        else lim = a.view == 0 ? K : min(K, irow + 1);  // in-block tile: K rows, causal for the AR view
-        if constexpr (PREFILL) lim = min(lim, pos0 + irow + 1 - i * 32);  // causal: tokens up to the row's own
-
-        f32x16 s;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-        Frag kf[KSTEPS];  // all K operand reads are issued before the first product needs one
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) kf[kk].n = *(const lds_u32x4 *)(uintptr_t)(ka[kk >> 1] + ((kk & 1) << 5));
-        __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products (the scheduler would pair them up)
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk].v, qf[kk].v, s, 0, 0, 0);
-        // first half of the V operand reads goes out now, so that their latency hides behind the softmax
-        constexpr int VPRE = DBLK / 2;
-        Frag vf[DBLK][2];
-#pragma unroll
-        for (int db = 0; db < VPRE; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                vf[db][q4 >> 1].h[q4 & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (lds_s16x4 *)(uintptr_t)(va_[db] + q4 * (8 / RPI) * GS));
-        __builtin_amdgcn_sched_barrier(0);
-        if (lim < 32) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int tok = 8 * (r >> 2) + 4 * h + (r & 3);  // S^T register r of this lane
-                if (tok >= lim) s[r] = -INFINITY;
-            }
-        }
-        float mx = s[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-        mx = max_with_other_half(mx);
-        // Online softmax with a lazily updated reference maximum (log2 domain): the reference only
-        // moves when the running maximum has grown by more than kLazy, so exponentials stay below
-        // 2^kLazy and the rescale of the accumulator is skipped for almost every tile.  The result
-        // is unchanged: numerator and denominator always share the same reference.
-        const float m_cand = fmaxf(m_run, mx * c);
-        if (__any(m_cand - m_run > kLazy)) {
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_cand);
-            m_run = m_cand;
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-        }
-        float p[16];
-        float sum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            p[r] = __builtin_amdgcn_exp2f(s[r] * c - m_run);
-            sum += p[r];
-        }
-        l_run += sum;
-        Frag p1, p2;
-        p1.u = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-        p2.u = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]),
-                          pack_bf16(p[14], p[15]));
-        // O^T += V^T P^T.  MFMA k-slot (h, j) of the first product is token 8*(j/4) + 4*h + j%4 (what
-        // registers 0..7 of S^T hold); the second product is 16 tokens further.
-#pragma unroll
-        for (int db = VPRE; db < DBLK; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                vf[db][q4 >> 1].h[q4 & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (lds_s16x4 *)(uintptr_t)(va_[db] + q4 * (8 / RPI) * GS));
-#pragma unroll
-        for (int db = 0; db < DBLK; ++db) {
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][0].v, p1.v, o[db], 0, 0, 0);
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][1].v, p2.v, o[db], 0, 0, 0);
-        }
-    }
-
-    // ---- write-out: this wave's 32 rows
-    l_run = sum_with_other_half(l_run);
-    if (PREFILL || a.num_splits == 1) {
+    const float c = a.scale_log2e;
+    for (;;) {  // one pass per work item (balanced mode: per segment)
+        // Queries: B operand of S^T = K.Q^T, lane holds row `col` of this wave's block,
+        // d = 16*kk + 8*h .. +7 (fetched while the loader's first tiles are in flight)
+        Frag qf[KSTEPS];
+        int irow;
+        const int ridx = wave * 32 + col;
+        // the lane's row exists: inside the R rows and, for prefill, inside the chunk's live tokens
+        const bool row_ok = ridx < a.rows && (!PREFILL || ridx / G < rows_live);
+        // row of q / out that holds block row (or new token) i of this sequence
+        const int64_t row_base = PREFILL ? (int64_t)b * a.max_new + row0 : (int64_t)b * K;
         if (row_ok) {
-            const int i = irow, hl = ridx - i * G;
-            const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
-            uint16_t *op = a.out + ((row_base + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
+            const int i = ridx / G, hl = ridx - i * G;
+            irow = i;
+            const uint16_t *qp = a.q + ((row_base + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
 #pragma unroll
-            for (int db = 0; db < DBLK; ++db)
+            for (int kk = 0; kk < KSTEPS; ++kk) qf[kk].u = *(const uint4 *)(qp + kk * 16 + h * 8);
+        } else {
+            irow = 31;  // padding rows see every in-block key; their output is never stored
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    uint2 pk;
-                    pk.x = pack_bf16(o[db][4 * r4] * inv, o[db][4 * r4 + 1] * inv);
-                    pk.y = pack_bf16(o[db][4 * r4 + 2] * inv, o[db][4 * r4 + 3] * inv);
-                    *(uint2 *)(op + 32 * db + 8 * r4 + 4 * h) = pk;
-                }
-            if (a.lse && h == 0)
-                a.lse[((int64_t)b * a.num_q_heads + (int64_t)g * G + hl) * K + i] =
-                    (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
+            for (int kk = 0; kk < KSTEPS; ++kk) qf[kk].u = make_uint4(0, 0, 0, 0);
         }
-    } else {
-        // partial in register order: [unit][split][wave][db][r4][lane] float4, then (m, l) per row
-        const size_t unit = (size_t)b * a.num_kv_heads + g;
-        const size_t slot = (unit * a.num_splits + split) * W + wave;
-        float4 *po = (float4 *)a.part_o + slot * (DBLK * 4 * 64) + lane;
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the queries are in registers before the loop starts
+
+        f32x16 o[DBLK];
 #pragma unroll
         for (int db = 0; db < DBLK; ++db)
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4)
-                po[(db * 4 + r4) * 64] =
-                    make_float4(o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]);
-        if (h == 0) ((float2 *)a.part_ml)[slot * 32 + col] = make_float2(m_run, l_run);
+            for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+        float m_run = kNegBig, l_run = 0.f;
+
+        // ---- main loop: one barrier per tile
+        int stage = 0;  // ring slot of tile i (= i % NS)
+        for (int i = 0; i < n_tiles; ++i) {
+            wg_barrier();
+
+            // LDS addresses of this tile's operands: one add per base, the rest are instruction offsets
+            const uint32_t st_addr = smem_lds + (uint32_t)stage * STAGE_B;
+            stage = stage + 1 == NS ? 0 : stage + 1;
+            uint32_t ka[KSTEPS / 2], va_[DBLK];
+#pragma unroll
+            for (int q = 0; q < KSTEPS / 2; ++q) ka[q] = st_addr + kb[q];
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db) va_[db] = st_addr + vb[db];
+            // lim = number of leading tile tokens this lane's row may see
+            int lim = 32;
+            if (i < n_cache) lim = t_end - (t_begin + i * 32);
+            else lim = a.view == 0 ? K : min(K, irow + 1);  // in-block tile: K rows, causal for the AR view
+            if constexpr (PREFILL) lim = min(lim, pos0 + irow + 1 - i * 32);  // causal: tokens up to the row's own
+
+            f32x16 s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+            Frag kf[KSTEPS];  // all K operand reads are issued before the first product needs one
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) kf[kk].n = *(const lds_u32x4 *)(uintptr_t)(ka[kk >> 1] + ((kk & 1) << 5));
+            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products (the scheduler would pair them up)
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk].v, qf[kk].v, s, 0, 0, 0);
+            // first half of the V operand reads goes out now, so that their latency hides behind the softmax
+            constexpr int VPRE = DBLK / 2;
+            Frag vf[DBLK][2];
+#pragma unroll
+            for (int db = 0; db < VPRE; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    vf[db][q4 >> 1].h[q4 & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (lds_s16x4 *)(uintptr_t)(va_[db] + q4 * (8 / RPI) * GS));
+            __builtin_amdgcn_sched_barrier(0);
+            if (lim < 32) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int tok = 8 * (r >> 2) + 4 * h + (r & 3);  // S^T register r of this lane
+                    if (tok >= lim) s[r] = -INFINITY;
+                }
+            }
+            float mx = s[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+            mx = max_with_other_half(mx);
+            // Online softmax with a lazily updated reference maximum (log2 domain): the reference only
+            // moves when the running maximum has grown by more than kLazy, so exponentials stay below
+            // 2^kLazy and the rescale of the accumulator is skipped for almost every tile.  The result
+            // is unchanged: numerator and denominator always share the same reference.
+            const float m_cand = fmaxf(m_run, mx * c);
+            if (__any(m_cand - m_run > kLazy)) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_cand);
+                m_run = m_cand;
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+            }
+            float p[16];
+            float sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                p[r] = __builtin_amdgcn_exp2f(s[r] * c - m_run);
+                sum += p[r];
+            }
+            l_run += sum;
+            Frag p1, p2;
+            p1.u = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+            p2.u = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]),
+                              pack_bf16(p[14], p[15]));
+            // O^T += V^T P^T.  MFMA k-slot (h, j) of the first product is token 8*(j/4) + 4*h + j%4 (what
+            // registers 0..7 of S^T hold); the second product is 16 tokens further.
+#pragma unroll
+            for (int db = VPRE; db < DBLK; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    vf[db][q4 >> 1].h[q4 & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (lds_s16x4 *)(uintptr_t)(va_[db] + q4 * (8 / RPI) * GS));
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db) {
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][0].v, p1.v, o[db], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][1].v, p2.v, o[db], 0, 0, 0);
+            }
+        }
+
+        // ---- write-out: this wave's 32 rows
+        l_run = sum_with_other_half(l_run);
+        if (final_out) {
+            if (row_ok) {
+                const int i = irow, hl = ridx - i * G;
+                const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+                uint16_t *op = a.out + ((row_base + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        uint2 pk;
+                        pk.x = pack_bf16(o[db][4 * r4] * inv, o[db][4 * r4 + 1] * inv);
+                        pk.y = pack_bf16(o[db][4 * r4 + 2] * inv, o[db][4 * r4 + 3] * inv);
+                        *(uint2 *)(op + 32 * db + 8 * r4 + 4 * h) = pk;
+                    }
+                if (a.lse && h == 0)
+                    a.lse[((int64_t)b * a.num_q_heads + (int64_t)g * G + hl) * K + i] =
+                        (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
+            }
+        } else {
+            // partial in register order: [partial][wave][db][r4][lane] float4, then (m, l) per row
+            const size_t slot = part_slot * W + wave;
+            float4 *po = (float4 *)a.part_o + slot * (DBLK * 4 * 64) + lane;
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4)
+                    po[(db * 4 + r4) * 64] =
+                        make_float4(o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]);
+            if (h == 0) ((float2 *)a.part_ml)[slot * 32 + col] = make_float2(m_run, l_run);
+        }
+        if (!BALANCED || !open_item()) break;
+        wg_barrier();  // matches the loader's barrier between segments
     }
 }
 
@@ -483,7 +594,12 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
 // KV head, 32-row block, 32-wide d block), one wave per group of 4 d values: a lane reads exactly the
 // float4 it would hold in the split kernel's accumulator, so every load is a contiguous 1 KB per wave
 // and all splits of a chunk are in flight together.
-template <int D, int W>
+//
+// BALANCED = 1: the pieces of a unit are found from the split kernel's partition arithmetic (NWG is
+// that launch's workgroup count): unit (g, b) covers tiles [U0, U1) of the launch's tile sequence,
+// its pieces belong to workgroups w_lo..w_hi, the first in its slot 2w+1 and the others in slot 2w;
+// a unit held by one workgroup was finished by the split kernel.
+template <int D, int W, int BALANCED = 0>
 __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
 {
     constexpr int DBLK = D / 32;
@@ -495,20 +611,65 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
     const int unit = blockIdx.x / (DBLK * W);
     const int b = unit / a.num_kv_heads, g = unit % a.num_kv_heads;
     const int ridx = wave * 32 + col;
-    int L = ((const const_i32 *)a.seq_lens)[b];
-    L = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
-    int live = (L + a.chunk_tokens - 1) / a.chunk_tokens;
-    live = live < 1 ? 1 : (live > a.num_splits ? a.num_splits : live);
-    const size_t slot0 = ((size_t)unit * a.num_splits) * W + wave;
-    const float2 *ml = (const float2 *)a.part_ml + slot0 * 32 + col;       // + s * W * 32
-    const float4 *po = (const float4 *)a.part_o + slot0 * (DBLK * 4 * 64) + (size_t)(db * 4 + r4) * 64 + lane;
-    const size_t po_stride = (size_t)W * (DBLK * 4 * 64), ml_stride = (size_t)W * 32;
+    int live;           // number of partials of this unit
+    size_t first_slot;  // partial index of piece 0; piece s > 0 sits at rest_slot + s * slot_step
+    size_t rest_slot, slot_step;
+    if constexpr (BALANCED) {
+        int before = 0, per_head = 0, mine = 0;  // tiles of the sequences before b, of all, of b
+        for (int x0 = 0; x0 < a.batch; x0 += 64) {
+            const int x = x0 + lane;
+            int n = 0;
+            if (x < a.batch) {
+                int L = a.seq_lens[x];
+                L = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
+                n = ((L + 31) >> 5) + 1;
+            }
+            int nb = x < b ? n : 0, nm = x == b ? n : 0;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                n += __shfl_xor(n, off);
+                nb += __shfl_xor(nb, off);
+                nm += __shfl_xor(nm, off);
+            }
+            per_head += n;
+            before += nb;
+            mine += nm;
+        }
+        const int64_t total = (int64_t)per_head * a.num_kv_heads;
+        const int64_t nwg = total < (int64_t)a.bal_wgs ? total : (int64_t)a.bal_wgs;
+        const int64_t U0 = (int64_t)g * per_head + before, U1 = U0 + mine;
+        // workgroup w starts at tile floor(w * total / nwg): w_lo is the last one that starts at or
+        // before U0, w_hi the last one that starts before U1
+        const int64_t w_lo = ((U0 + 1) * nwg + total - 1) / total - 1;
+        const int64_t w_hi = (U1 * nwg + total - 1) / total - 1;
+        if (w_lo == w_hi) return;  // one workgroup held the whole unit and wrote its rows
+        live = (int)(w_hi - w_lo + 1);
+        first_slot = (size_t)w_lo * 2 + 1;
+        rest_slot = (size_t)w_lo * 2;
+        slot_step = 2;
+    } else {
+        int L = ((const const_i32 *)a.seq_lens)[b];
+        L = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
+        live = (L + a.chunk_tokens - 1) / a.chunk_tokens;
+        live = live < 1 ? 1 : (live > a.num_splits ? a.num_splits : live);
+        first_slot = rest_slot = (size_t)unit * a.num_splits;
+        slot_step = 1;
+    }
+    // partial `s` of this unit: (m, l) of the lane's row and the lane's float4 of the accumulator
+    auto ml_at = [&](int s) __attribute__((always_inline)) {
+        const size_t slot = (s == 0 ? first_slot : rest_slot + (size_t)s * slot_step) * W + wave;
+        return (const float2 *)a.part_ml + slot * 32 + col;
+    };
+    auto po_at = [&](int s) __attribute__((always_inline)) {
+        const size_t slot = (s == 0 ? first_slot : rest_slot + (size_t)s * slot_step) * W + wave;
+        return (const float4 *)a.part_o + slot * (DBLK * 4 * 64) + (size_t)(db * 4 + r4) * 64 + lane;
+    };
 
     float M = kNegBig;
     for (int s0 = 0; s0 < live; s0 += CHUNK) {
         float mv[CHUNK];
 #pragma unroll
-        for (int u = 0; u < CHUNK; ++u) mv[u] = (s0 + u < live) ? ml[(size_t)(s0 + u) * ml_stride].x : kNegBig;
+        for (int u = 0; u < CHUNK; ++u) mv[u] = (s0 + u < live) ? ml_at(s0 + u)->x : kNegBig;
 #pragma unroll
         for (int u = 0; u < CHUNK; ++u) M = fmaxf(M, mv[u]);
     }
@@ -520,8 +681,8 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
 #pragma unroll
         for (int u = 0; u < CHUNK; ++u) {
             const bool ok = s0 + u < live;
-            v[u] = ok ? po[(size_t)(s0 + u) * po_stride] : make_float4(0.f, 0.f, 0.f, 0.f);
-            e[u] = ok ? ml[(size_t)(s0 + u) * ml_stride] : make_float2(kNegBig, 0.f);
+            v[u] = ok ? *po_at(s0 + u) : make_float4(0.f, 0.f, 0.f, 0.f);
+            e[u] = ok ? *ml_at(s0 + u) : make_float2(kNegBig, 0.f);
         }
 #pragma unroll
         for (int u = 0; u < CHUNK; ++u) {  // fixed split order: the result does not depend on timing
@@ -561,8 +722,7 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
 {
     const int R = group * block_k;
     plan->rows = R;
-    int W = 1;
-    while (W * 32 < R) W *= 2;
+    const int W = R > 32 ? (R + 31) / 32 : 1;
     plan->waves = W;
     plan->rows_padded = W * 32;
     plan->lds_bytes = lds_need(head_dim);
@@ -572,6 +732,16 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     int per_cu = (int)(160 * 1024 / plan->lds_bytes);
     if (per_cu > 12 / (W + 1)) per_cu = 12 / (W + 1);
     if (per_cu < 1) per_cu = 1;
+    plan->bal_wgs = 0;
+    if (requested_splits < 0) {
+        // balanced partition: as many workgroups as are resident at once, two partial slots each
+        plan->bal_wgs = num_cus * per_cu;
+        plan->chunk_tokens = 32;
+        plan->num_splits = 1;
+        plan->part_o_bytes = (size_t)plan->bal_wgs * 2 * plan->rows_padded * head_dim * sizeof(float);
+        plan->part_ml_bytes = (size_t)plan->bal_wgs * 2 * plan->rows_padded * 2 * sizeof(float);
+        return hipSuccess;
+    }
     int splits;
     if (requested_splits > 0) {
         splits = requested_splits;
@@ -618,12 +788,15 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     return hipSuccess;
 }
 
-template <int D, int W>
+// One attention call: the split kernel, then the merge when units were cut into pieces.
+template <int D, int W, int BALANCED>
 static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStream_t stream, AttnLaunchEvents *ev)
 {
-    auto kern = attn_split_kernel<D, W, kStages>;
+    auto kern = attn_split_kernel<D, W, kStages, 0, BALANCED>;
+    auto comb = attn_combine_kernel<D, W, BALANCED>;
     const bool timed = ev && ev->on;
-    dim3 grid((unsigned)plan.num_splits * (unsigned)a.num_kv_heads * (unsigned)a.batch);
+    dim3 grid(BALANCED ? (unsigned)plan.bal_wgs
+                       : (unsigned)plan.num_splits * (unsigned)a.num_kv_heads * (unsigned)a.batch);
     dim3 block(64 * (W + 1));
     if (timed) {
         hipExtLaunchKernelGGL(kern, grid, block, plan.lds_bytes, stream, ev->start[0], ev->stop[0], 0, a);
@@ -633,14 +806,13 @@ static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStr
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (plan.num_splits > 1) {
+    if (BALANCED || plan.num_splits > 1) {
         dim3 cgrid((unsigned)(a.batch * a.num_kv_heads) * W * (D / 32));
         if (timed) {
-            hipExtLaunchKernelGGL((attn_combine_kernel<D, W>), cgrid, dim3(256), 0, stream, ev->start[1], ev->stop[1],
-                                  0, a);
+            hipExtLaunchKernelGGL(comb, cgrid, dim3(256), 0, stream, ev->start[1], ev->stop[1], 0, a);
             ev->used[1] = true;
         } else {
-            hipLaunchKernelGGL((attn_combine_kernel<D, W>), cgrid, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(comb, cgrid, dim3(256), 0, stream, a);
         }
         e = hipGetLastError();
     }
@@ -656,21 +828,43 @@ static hipError_t launch_prefill_variant(const AttnArgs &a, size_t lds_bytes, hi
 }
 
 // Prefill attention: a.num_splits carries the number of 32-token chunks per sequence, a.rows = 32 * group.
+template <int D>
+static hipError_t launch_prefill_d(const AttnArgs &a, size_t lds, hipStream_t stream)
+{
+    switch (a.group) {  // one compute wave per query head of the group
+    case 1: return launch_prefill_variant<D, 1>(a, lds, stream);
+    case 2: return launch_prefill_variant<D, 2>(a, lds, stream);
+    case 3: return launch_prefill_variant<D, 3>(a, lds, stream);
+    case 4: return launch_prefill_variant<D, 4>(a, lds, stream);
+    case 5: return launch_prefill_variant<D, 5>(a, lds, stream);
+    case 6: return launch_prefill_variant<D, 6>(a, lds, stream);
+    case 7: return launch_prefill_variant<D, 7>(a, lds, stream);
+    case 8: return launch_prefill_variant<D, 8>(a, lds, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_prefill_attn(const AttnArgs &a, int head_dim, hipStream_t stream)
 {
     if (a.batch == 0 || a.num_splits == 0) return hipSuccess;
-    int W = 1;
-    while (W < a.group) W *= 2;
     const size_t lds = lds_need(head_dim);
-    switch (head_dim * 10 + W) {
-    case 1281: return launch_prefill_variant<128, 1>(a, lds, stream);
-    case 1282: return launch_prefill_variant<128, 2>(a, lds, stream);
-    case 1284: return launch_prefill_variant<128, 4>(a, lds, stream);
-    case 1288: return launch_prefill_variant<128, 8>(a, lds, stream);
-    case 641: return launch_prefill_variant<64, 1>(a, lds, stream);
-    case 642: return launch_prefill_variant<64, 2>(a, lds, stream);
-    case 644: return launch_prefill_variant<64, 4>(a, lds, stream);
-    case 648: return launch_prefill_variant<64, 8>(a, lds, stream);
+    if (head_dim == 128) return launch_prefill_d<128>(a, lds, stream);
+    if (head_dim == 64) return launch_prefill_d<64>(a, lds, stream);
+    return hipErrorInvalidValue;
+}
+
+template <int D, int BALANCED>
+static hipError_t launch_attn_d(const AttnArgs &a, const AttnPlan &plan, hipStream_t stream, AttnLaunchEvents *events)
+{
+    switch (plan.waves) {
+    case 1: return launch_variant<D, 1, BALANCED>(a, plan, stream, events);
+    case 2: return launch_variant<D, 2, BALANCED>(a, plan, stream, events);
+    case 3: return launch_variant<D, 3, BALANCED>(a, plan, stream, events);
+    case 4: return launch_variant<D, 4, BALANCED>(a, plan, stream, events);
+    case 5: return launch_variant<D, 5, BALANCED>(a, plan, stream, events);
+    case 6: return launch_variant<D, 6, BALANCED>(a, plan, stream, events);
+    case 7: return launch_variant<D, 7, BALANCED>(a, plan, stream, events);
+    case 8: return launch_variant<D, 8, BALANCED>(a, plan, stream, events);
     }
     return hipErrorInvalidValue;
 }
@@ -679,17 +873,11 @@ hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hi
                        AttnLaunchEvents *events)
 {
     if (a.batch == 0) return hipSuccess;
-    const int key = head_dim * 10 + plan.waves;
-    switch (key) {
-    case 1281: return launch_variant<128, 1>(a, plan, stream, events);
-    case 1282: return launch_variant<128, 2>(a, plan, stream, events);
-    case 1284: return launch_variant<128, 4>(a, plan, stream, events);
-    case 1288: return launch_variant<128, 8>(a, plan, stream, events);
-    case 641: return launch_variant<64, 1>(a, plan, stream, events);
-    case 642: return launch_variant<64, 2>(a, plan, stream, events);
-    case 644: return launch_variant<64, 4>(a, plan, stream, events);
-    case 648: return launch_variant<64, 8>(a, plan, stream, events);
-    }
+    const bool bal = plan.bal_wgs > 0;
+    if (head_dim == 128)
+        return bal ? launch_attn_d<128, 1>(a, plan, stream, events) : launch_attn_d<128, 0>(a, plan, stream, events);
+    if (head_dim == 64)
+        return bal ? launch_attn_d<64, 1>(a, plan, stream, events) : launch_attn_d<64, 0>(a, plan, stream, events);
     return hipErrorInvalidValue;
 }
 

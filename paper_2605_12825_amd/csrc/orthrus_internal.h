@@ -10,12 +10,13 @@ constexpr float kNegBig = -1.0e30f;
 
 struct AttnPlan {
     int rows;          // R = G * K query rows per KV head
-    int waves;         // waves per workgroup = 32-row blocks (1, 2, 4 or 8)
+    int waves;         // compute waves per workgroup = 32-row blocks (1 .. 8)
     int rows_padded;   // waves * 32
     int chunk_tokens;  // cache tokens per split (multiple of 32)
     int num_splits;    // splits per (sequence, KV head)
+    int bal_wgs;       // > 0: balanced partition over this many workgroups instead of fixed splits
     size_t lds_bytes;  // dynamic LDS per workgroup
-    size_t part_o_bytes, part_ml_bytes;  // workspace pieces (0 when num_splits == 1)
+    size_t part_o_bytes, part_ml_bytes;  // workspace pieces (0 when nothing is merged)
 };
 
 struct AttnArgs {
@@ -23,8 +24,9 @@ struct AttnArgs {
     const int32_t *page_table, *seq_lens;
     uint16_t *out;
     float *lse;
-    float *part_o;   // [unit][split][wave][d block][4][lane] float4: unnormalised partial outputs, register order
-    float *part_ml;  // [unit][split][wave][32 rows] float2: running max (log2 domain) and sum
+    // partial p = (unit, split), or workgroup slot 2w / 2w+1 of the balanced partition
+    float *part_o;   // [p][wave][d block][4][lane] float4: unnormalised partial outputs, register order
+    float *part_ml;  // [p][wave][32 rows] float2: running max (log2 domain) and sum
     int32_t *err_word;
     // prefill only: lengths before the call and validated new-token counts [B] (workspace), row stride T
     const int32_t *old_lens, *new_lens;
@@ -32,6 +34,7 @@ struct AttnArgs {
     int64_t stride_page, stride_head, stride_tok, num_pages;
     int batch, num_q_heads, num_kv_heads, group, block_k, rows;
     int page_shift, max_pages_per_seq, max_seq_len, chunk_tokens, num_splits, view;
+    int bal_wgs;  // balanced partition: workgroups of the split launch (0 otherwise)
     float scale_log2e;  // sm_scale * log2(e)
 };
 

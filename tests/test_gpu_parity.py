@@ -118,10 +118,13 @@ SMALL = [
     dict(batch=1, num_q_heads=16, num_kv_heads=2, head_dim=64, block_k=32, context=333, page_size=64),
     dict(batch=4, num_q_heads=3, num_kv_heads=1, head_dim=128, block_k=5, context_range=(0, 130), page_size=16),
     dict(batch=1, num_q_heads=5, num_kv_heads=5, head_dim=128, block_k=7, context=1025, page_size=16),
+    # five and six 32-row blocks per KV head
+    dict(batch=2, num_q_heads=5, num_kv_heads=1, head_dim=128, block_k=32, context_range=(40, 500), page_size=16),
+    dict(batch=2, num_q_heads=12, num_kv_heads=2, head_dim=64, block_k=31, context_range=(0, 300), page_size=16),
 ]
 
 
-@pytest.mark.parametrize("splits", [0, 1, 3])
+@pytest.mark.parametrize("splits", [0, 1, 3, -1])  # -1: the balanced partition
 @pytest.mark.parametrize("shape", range(len(SMALL)))
 def test_small_shapes_attention(shape, splits):
     kw = dict(name="s%d" % shape, seed=300 + shape, paging="shuffled")
@@ -142,11 +145,12 @@ def test_edge_lengths(L):
     w = Workload(name="edge", batch=2, num_q_heads=8, num_kv_heads=2, head_dim=128, block_k=8, context=L,
                  page_size=16, seed=40 + L)
     cache = make_cache(w, seq_lens=np.array([L, max(0, L - 1)], np.int32))
-    case = GpuCase(w, cache, max_seq_len=max(L, 1))
-    for view in (DIFF, AR):
-        blk = make_block(w, 500 + L + view)
-        got = case.attn(view, blk, want_lse=False)
-        _check_attn(got, _oracle_attn(view, w, blk, cache), "L=%d view %d" % (L, view))
+    for splits in (0, -1):
+        case = GpuCase(w, cache, max_seq_len=max(L, 1), num_splits=splits)
+        for view in (DIFF, AR):
+            blk = make_block(w, 500 + L + view)
+            got = case.attn(view, blk, want_lse=False)
+            _check_attn(got, _oracle_attn(view, w, blk, cache), "L=%d view %d splits %d" % (L, view, splits))
 
 
 def test_split_count_invariance_and_determinism():
@@ -156,7 +160,7 @@ def test_split_count_invariance_and_determinism():
     blk = make_block(w, 78)
     want = _oracle_attn(AR, w, blk, cache)
     outs = {}
-    for s in (1, 2, 7, 64):
+    for s in (1, 2, 7, 64, -1):
         case = GpuCase(w, cache, num_splits=s)
         outs[s] = case.attn(AR, blk, want_lse=False)
         _check_attn(outs[s], want, "splits %d" % s)
@@ -187,11 +191,12 @@ def _sub_batch(blk, cache, idx):
     return b, c
 
 
-def test_mixed_config_attention_sampled_sequences():
+@pytest.mark.parametrize("splits", [0, -1])
+def test_mixed_config_attention_sampled_sequences(splits):
     """Full-size batched mixed-length run; the oracle recomputes the shortest, the longest and one more sequence."""
     w = WORKLOADS["mixed"]
     cache = make_cache(w)
-    case = GpuCase(w, cache)
+    case = GpuCase(w, cache, num_splits=splits)
     lens = cache["seq_lens"]
     pick = sorted({int(np.argmin(lens)), int(np.argmax(lens)), 5})
     for view in (DIFF, AR):

@@ -72,6 +72,8 @@ SHAPES = [
     (dict(batch=1, num_q_heads=8, num_kv_heads=1, head_dim=64, context=0, page_size=64), 100, [100]),
     (dict(batch=4, num_q_heads=6, num_kv_heads=2, head_dim=128, context_range=(0, 40), page_size=16), 32, [1, 32, 31, 2]),
     (dict(batch=1, num_q_heads=2, num_kv_heads=2, head_dim=128, context=0, page_size=16), 1, [1]),
+    (dict(batch=2, num_q_heads=5, num_kv_heads=1, head_dim=128, context_range=(3, 70), page_size=16), 45, [45, 20]),
+    (dict(batch=2, num_q_heads=12, num_kv_heads=2, head_dim=64, context_range=(0, 50), page_size=16), 33, [33, 32]),
 ]
 
 
