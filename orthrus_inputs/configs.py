@@ -30,7 +30,7 @@ class Workload:
     accept: str = "geometric"           # "uniform" (0..K) or "geometric" (p below, capped at K)
     accept_p: float = 0.3
     steps: int = 1                      # looped decode steps (cache grows by the committed counts)
-    num_splits: int = 0                 # 0 = library picks
+    num_splits: int = 0                 # 0 = library picks; -1 = balanced partition (ragged batches)
     seed: int = 0
     description: str = ""
 
@@ -64,7 +64,7 @@ WORKLOADS = {
         description="batch 1, 32/8 heads, d=128, context 4096, K=16, shuffled 16-token pages, vocab 128256"),
     "mixed": Workload(
         name="mixed", batch=16, num_q_heads=28, num_kv_heads=4, head_dim=128, block_k=32,
-        context_range=(512, 8192), paging="scattered", vocab=0, seed=1002,
+        context_range=(512, 8192), paging="scattered", vocab=0, seed=1002, num_splits=-1,
         description="batch 16, 28/4 heads, d=128, context U[512,8192], K=32, pages scattered in a shared pool"),
     "long": Workload(
         name="long", batch=4, num_q_heads=32, num_kv_heads=8, head_dim=128, block_k=16,

@@ -117,8 +117,8 @@ struct AttnGeom {
 // else.  A wave that issues global->LDS loads is held up while the memory pipeline takes them
 // (streaming 2 MB per CU costs the issuing wave about as long as the arithmetic on it costs a compute
 // wave), so when compute waves issue their own loads the two costs add up; with a dedicated loader
-// wave they overlap.  The compute waves stay below 168 registers, so W + 1 <= 9 waves fit a CU at
-// three waves per SIMD.
+// wave they overlap.  The register budget is 168 (three waves per SIMD), so W + 1 <= 9 waves fit a CU;
+// the balanced form spills a dozen values that live across segments, outside the tile loop.
 //
 // PREFILL = 1 turns the same kernel into the AR view's causal prefill attention (Section 3.1): the new
 // tokens' K/V rows are already in the cache, a work item is (sequence, chunk of 32 new tokens, KV head),
@@ -135,7 +135,7 @@ struct AttnGeom {
 // still gets the same number of tiles, and with N = resident workgroups nothing queues behind
 // the dispatcher.  Each segment runs the pipeline from empty (fill, loop, drain).
 template <int D, int W, int NS, int PREFILL = 0, int BALANCED = 0>
-__global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnArgs a)
+__global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnArgs a)
 {
     static_assert(!(PREFILL && BALANCED), "the balanced partition is a decode mode");
     using Gm = AttnGeom<D>;
@@ -200,8 +200,8 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
         const int64_t nwg = total < (int64_t)gridDim.x ? total : (int64_t)gridDim.x;
         if ((int64_t)blockIdx.x >= nwg) return;
         const int64_t c0 = (int64_t)blockIdx.x * total / nwg, c1 = ((int64_t)blockIdx.x + 1) * total / nwg;
-        bal_left = (int)(c1 - c0);
-        bal_g = (int)(c0 / per_head);
+        bal_left = __builtin_amdgcn_readfirstlane((int)(c1 - c0));
+        bal_g = __builtin_amdgcn_readfirstlane((int)(c0 / per_head));
         const int r = (int)(c0 - (int64_t)bal_g * per_head);
         // the sequence whose tiles contain offset r of the head: inclusive scan over 64 sequences at a time
         int base = 0;
@@ -237,18 +237,22 @@ __global__ void __launch_bounds__(64 * (W + 1), 2) attn_split_kernel(const AttnA
             const int nc = (L + 31) >> 5;                    // cache tiles of the unit; the in-block tile is tile nc
             const int take = min(nc + 1 - bal_o, bal_left);  // tiles of this segment
             const bool has_blk = bal_o + take == nc + 1;
-            n_tiles = take;
-            n_cache = has_blk ? take - 1 : take;
-            t_begin = bal_o * 32;
+            // (everything here is wave-uniform; readfirstlane keeps it in scalar registers)
+            n_tiles = __builtin_amdgcn_readfirstlane(take);
+            n_cache = has_blk ? n_tiles - 1 : n_tiles;
+            t_begin = __builtin_amdgcn_readfirstlane(bal_o * 32);
             t_end = min(L, t_begin + n_cache * 32);
             final_out = bal_o == 0 && has_blk;
-            part_slot = (size_t)blockIdx.x * 2 + (bal_o == 0 ? 1 : 0);
-            bal_left -= take;
+            part_slot = (size_t)(blockIdx.x * 2u + (bal_o == 0 ? 1u : 0u));
+            bal_left = __builtin_amdgcn_readfirstlane(bal_left - take);
             bal_o = 0;
-            if (++bal_b == a.batch) {
-                bal_b = 0;
-                ++bal_g;
+            int nb = bal_b + 1, ng = bal_g;
+            if (nb == a.batch) {
+                nb = 0;
+                ++ng;
             }
+            bal_b = __builtin_amdgcn_readfirstlane(nb);
+            bal_g = __builtin_amdgcn_readfirstlane(ng);
         } else {
             // Workgroup id -> (sequence, split, KV head) with the sequence index fastest and the head
             // slowest.  Consecutive workgroup ids go to different XCDs; a head's rows sit at a fixed

@@ -85,6 +85,22 @@ def test_split_planning_aims_at_one_workgroup_per_cu():
     assert orthrus.orthrus_attn_workspace_bytes(p) >= 4 * 8 * 64 * rows * (d + 2) * 4
 
 
+def test_balanced_partition_plan_on_the_host():
+    """num_splits = -1: no fixed split count, workspace = two partials per resident workgroup, whatever the lengths."""
+    from orthrus_inputs import WORKLOADS
+    p = _params_for(WORKLOADS["mixed"], 8192)
+    p.num_splits = -1
+    assert orthrus.orthrus_attn_num_splits(p) == 0
+    rows, d, wgs = 7 * 32, 128, 256              # R = 224 rows in 7 blocks: 8 waves, one workgroup per CU
+    want = 2 * wgs * rows * (d + 2) * 4
+    assert want <= orthrus.orthrus_attn_workspace_bytes(p) <= want + 512
+    p.max_seq_len = 512
+    assert want <= orthrus.orthrus_attn_workspace_bytes(p) <= want + 512
+    p.num_splits = -2
+    with pytest.raises(orthrus.OrthrusError):
+        orthrus.orthrus_attn_num_splits(p)
+
+
 def test_prefill_workspace_and_argument_checks_on_the_host():
     p = _good()
     assert orthrus.orthrus_prefill_workspace_bytes(p, 4096) >= 2 * 4 * p.batch
