@@ -173,7 +173,7 @@ def run_prefill(args, torch, rt, w):
     print(json.dumps(res), flush=True)
 
 
-def run_train_mask(args, torch, rt, w):
+def run_train_mask(args, torch, rt, w, splits):
     """Forward of the diffusion view under the training block mask (Section 3.2 Eq. 6, Appendix A geometry):
     every anchor block is one batch entry of orthrus_dual_view_attn(DIFFUSION) over the clean context before
     its anchor; the context's K/V stay in their plain [tokens, H_kv, d] layout (described by the pool strides)."""
@@ -192,7 +192,7 @@ def run_train_mask(args, torch, rt, w):
     k_ar, v_ar = D(mk(NS * L, Hkv)), D(mk(NS * L, Hkv))
     out = torch.empty_like(q)
     step = rt.DecodeStep(batch=NS * NB, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d, block_k=K, page_size=P,
-                         max_pages_per_seq=pages, max_seq_len=L, num_pages=NS * pages,
+                         max_pages_per_seq=pages, max_seq_len=L, num_pages=NS * pages, num_splits=splits,
                          pool_strides=(0, P * Hkv * d, d, Hkv * d))
     pt, sl = D(np.ascontiguousarray(page_table)), D(anchors.reshape(-1))
     stream = torch.cuda.current_stream()
@@ -218,7 +218,7 @@ def run_train_mask(args, torch, rt, w):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%d packed sequences of %d tokens, %d anchor blocks of K=%d each, %s head shapes" %
                                (NS, L, NB, K, w.name), "num_q_heads": Hq, "num_kv_heads": Hkv, "head_dim": d,
-                   "num_splits": step.num_splits},
+                   "num_splits": "balanced" if splits == -1 else step.num_splits},
         "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0, "unit": "TFLOP/s",
                      "frac": round(tf / 2500.0, 4), "traffic": None,
                      "kernel": "orthrus_dual_view_attn(DIFFUSION) with one batch entry per anchor block",
@@ -349,7 +349,7 @@ def main():
         run_prefill(args, torch, rt, WORKLOADS[args.workload])
         return
     if args.train_mask > 0:
-        run_train_mask(args, torch, rt, WORKLOADS[args.workload])
+        run_train_mask(args, torch, rt, WORKLOADS[args.workload], 0 if args.num_splits == "workload" else splits)
         return
     t_gen = time.perf_counter()
     cache = make_cache(w)
@@ -493,7 +493,7 @@ def main():
         "config": {"workload": w.name, "description": w.description, "batch": B, "num_q_heads": w.num_q_heads,
                    "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim, "block_k": K,
                    "context": int(lens_before.max()), "page_size": w.page_size, "vocab": w.vocab,
-                   "num_splits": step.num_splits, "layers": 1, "temperature": T,
+                   "num_splits": "balanced" if splits == -1 else step.num_splits, "layers": 1, "temperature": T,
                    "step": "diffusion attn + AR verify attn" +
                            ((" + sampling consensus + commit" if T > 0 else " + greedy consensus + commit")
                             if w.vocab else "")},
