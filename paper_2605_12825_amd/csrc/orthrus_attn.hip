@@ -603,11 +603,15 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
 // that launch's workgroup count): unit (g, b) covers tiles [U0, U1) of the launch's tile sequence,
 // its pieces belong to workgroups w_lo..w_hi, the first in its slot 2w+1 and the others in slot 2w;
 // a unit held by one workgroup was finished by the split kernel.
-template <int D, int W, int BALANCED = 0>
+//
+// CHUNK = partials merged per round of loads: 8 keeps the registers low for the bandwidth-bound merges
+// of many units with few pieces each; 16 halves the dependent round trips of a latency-bound merge of
+// few units with many splits.
+template <int D, int W, int BALANCED = 0, int CHUNK = 8>
 __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
 {
     constexpr int DBLK = D / 32;
-    constexpr int CHUNK = 8;
+    constexpr int MCHUNK = 32;  // m values fetched per round when there are more than CHUNK partials
     const int lane = threadIdx.x & 63, r4 = threadIdx.x >> 6;
     const int col = lane & 31, h = lane >> 5;
     const int db = blockIdx.x % DBLK;
@@ -669,25 +673,34 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
         return (const float4 *)a.part_o + slot * (DBLK * 4 * 64) + (size_t)(db * 4 + r4) * 64 + lane;
     };
 
-    float M = kNegBig;
-    for (int s0 = 0; s0 < live; s0 += CHUNK) {
-        float mv[CHUNK];
-#pragma unroll
-        for (int u = 0; u < CHUNK; ++u) mv[u] = (s0 + u < live) ? ml_at(s0 + u)->x : kNegBig;
-#pragma unroll
-        for (int u = 0; u < CHUNK; ++u) M = fmaxf(M, mv[u]);
-    }
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float lsum = 0.f;
-    for (int s0 = 0; s0 < live; s0 += CHUNK) {
-        float4 v[CHUNK];
-        float2 e[CHUNK];
+    // The loads of the first CHUNK partials go out before anything waits; the reference maximum needs
+    // every partial's m, so the remaining m values follow MCHUNK at a time, then the rest of the data.
+    // A merge of up to CHUNK partials is one memory round trip, not one per pass.
+    float4 v[CHUNK];
+    float2 e[CHUNK];
+    auto load_chunk = [&](int s0) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < CHUNK; ++u) {
             const bool ok = s0 + u < live;
             v[u] = ok ? *po_at(s0 + u) : make_float4(0.f, 0.f, 0.f, 0.f);
             e[u] = ok ? *ml_at(s0 + u) : make_float2(kNegBig, 0.f);
         }
+    };
+    load_chunk(0);
+    float M = kNegBig;
+#pragma unroll
+    for (int u = 0; u < CHUNK; ++u) M = fmaxf(M, e[u].x);
+    for (int s0 = CHUNK; s0 < live; s0 += MCHUNK) {
+        float mv[MCHUNK];
+#pragma unroll
+        for (int u = 0; u < MCHUNK; ++u) mv[u] = (s0 + u < live) ? ml_at(s0 + u)->x : kNegBig;
+#pragma unroll
+        for (int u = 0; u < MCHUNK; ++u) M = fmaxf(M, mv[u]);
+    }
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lsum = 0.f;
+    for (int s0 = 0; s0 < live; s0 += CHUNK) {
+        if (s0 > 0) load_chunk(s0);
 #pragma unroll
         for (int u = 0; u < CHUNK; ++u) {  // fixed split order: the result does not depend on timing
             const float sc = __builtin_amdgcn_exp2f(e[u].x - M);
@@ -797,7 +810,8 @@ template <int D, int W, int BALANCED>
 static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStream_t stream, AttnLaunchEvents *ev)
 {
     auto kern = attn_split_kernel<D, W, kStages, 0, BALANCED>;
-    auto comb = attn_combine_kernel<D, W, BALANCED>;
+    auto comb = (!BALANCED && plan.num_splits > 8) ? attn_combine_kernel<D, W, BALANCED, 16>
+                                                   : attn_combine_kernel<D, W, BALANCED, 8>;
     const bool timed = ev && ev->on;
     dim3 grid(BALANCED ? (unsigned)plan.bal_wgs
                        : (unsigned)plan.num_splits * (unsigned)a.num_kv_heads * (unsigned)a.batch);
