@@ -71,12 +71,13 @@ def _check_attn(got_bits, want):
     assert np.all(np.isfinite(got)) and err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
 
 
-def test_stack_cycle_eager_and_graph_replay_match_oracle():
+@pytest.mark.parametrize("splits", [0, -1])   # the library's fixed splits; the balanced partition
+def test_stack_cycle_eager_and_graph_replay_match_oracle(splits):
     w = _workload()
     kp, vp, pt, lens = _initial_state(w)
     ref_k, ref_v, ref_len = kp.copy(), vp.copy(), lens.copy()
-    eager = _make_stack(w, kp, vp, pt, lens)
-    graph = _make_stack(w, kp, vp, pt, lens)
+    eager = _make_stack(w, kp, vp, pt, lens, num_splits=splits)
+    graph = _make_stack(w, kp, vp, pt, lens, num_splits=splits)
     graph.capture()                       # records only: nothing has run, the state is still the initial one
     np.testing.assert_array_equal(graph.seq_lens.cpu().numpy(), lens)
     for c in range(CYCLES):
