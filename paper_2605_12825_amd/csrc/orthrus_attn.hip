@@ -36,6 +36,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
@@ -580,13 +581,14 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
         } else {
             // partial in register order: [partial][wave][db][r4][lane] float4, then (m, l) per row
             const size_t slot = part_slot * W + wave;
-            float4 *po = (float4 *)a.part_o + slot * (DBLK * 4 * 64) + lane;
+            f32x4 *po = (f32x4 *)a.part_o + slot * (DBLK * 4 * 64) + lane;
 #pragma unroll
             for (int db = 0; db < DBLK; ++db)
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4)
-                    po[(db * 4 + r4) * 64] =
-                        make_float4(o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]);
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4 v = {o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]};
+                    __builtin_nontemporal_store(v, &po[(db * 4 + r4) * 64]);
+                }
             if (h == 0) ((float2 *)a.part_ml)[slot * 32 + col] = make_float2(m_run, l_run);
         }
         if (!BALANCED || !open_item()) break;
