@@ -209,6 +209,7 @@ orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p,
     a.page_shift = log2_exact(p->page_size); a.max_pages_per_seq = p->max_pages_per_seq;
     a.max_seq_len = p->max_seq_len; a.chunk_tokens = plan.chunk_tokens; a.num_splits = plan.num_splits;
     a.bal_wgs = plan.bal_wgs;
+    a.kv_nt = plan.kv_nt;
     a.view = (int)view;
     a.scale_log2e = p->sm_scale * 1.4426950408889634f;
     orthrus::AttnLaunchEvents ev;
@@ -307,6 +308,7 @@ orthrus_status orthrus_prefill_attn(orthrus_ctx *ctx, const orthrus_params *p, i
     a.page_shift = f.page_shift; a.max_pages_per_seq = p->max_pages_per_seq;
     a.max_seq_len = p->max_seq_len; a.chunk_tokens = 0; a.num_splits = (int)chunks;
     a.bal_wgs = 0;
+    a.kv_nt = 0;  // every chunk of a sequence re-reads the same cache rows: keep them cached
     a.view = (int)ORTHRUS_VIEW_AR_VERIFY;
     a.scale_log2e = p->sm_scale * 1.4426950408889634f;
     e = orthrus::launch_prefill_attn(a, p->head_dim, (hipStream_t)stream);

@@ -15,6 +15,7 @@ struct AttnPlan {
     int chunk_tokens;  // cache tokens per split (multiple of 32)
     int num_splits;    // splits per (sequence, KV head)
     int bal_wgs;       // > 0: balanced partition over this many workgroups instead of fixed splits
+    int kv_nt;         // 1: the call streams more K/V than the last-level cache holds: non-temporal tile loads
     size_t lds_bytes;  // dynamic LDS per workgroup
     size_t part_o_bytes, part_ml_bytes;  // workspace pieces (0 when nothing is merged)
 };
@@ -35,6 +36,7 @@ struct AttnArgs {
     int batch, num_q_heads, num_kv_heads, group, block_k, rows;
     int page_shift, max_pages_per_seq, max_seq_len, chunk_tokens, num_splits, view;
     int bal_wgs;  // balanced partition: workgroups of the split launch (0 otherwise)
+    int kv_nt;    // non-temporal K/V tile loads (see AttnPlan)
     float scale_log2e;  // sm_scale * log2(e)
 };
 
