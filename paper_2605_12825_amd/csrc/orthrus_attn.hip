@@ -777,7 +777,7 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     if (per_cu < 1) per_cu = 1;
     plan->bal_wgs = 0;
     // K/V bytes one call streams at most, against the 256 MB last-level cache (see the kernel's loads)
-    plan->kv_nt = (double)batch * max_seq_len * num_kv_heads * 4.0 * head_dim > 1.5 * 256.0 * 1024 * 1024 ? 1 : 0;
+    plan->kv_nt = (double)batch * max_seq_len * num_kv_heads * 4.0 * head_dim > 1.25 * 256.0 * 1024 * 1024 ? 1 : 0;
     if (requested_splits < 0) {
         // balanced partition: as many workgroups as are resident at once, two partial slots each
         plan->bal_wgs = num_cus * per_cu;

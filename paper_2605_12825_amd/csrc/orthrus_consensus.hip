@@ -22,6 +22,8 @@
 
 namespace orthrus {
 
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
 constexpr int kChunkElems = 8192;  // floats per (row, chunk) workgroup: 32 KiB
 int consensus_chunk_elems() { return kChunkElems; }
 
@@ -92,7 +94,10 @@ __global__ void __launch_bounds__(256) argmax_partial_kernel(const ConsensusArgs
         for (int u = 0; u < NL; ++u) {
             const int i = begin + (u * 256 + tid) * 4;
             x[u] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-            if (i < end) x[u] = *(const float4 *)(base + i);
+            if (i < end) {  // read once, never again: do not let the row displace anything in the caches
+                const f32x4 v = __builtin_nontemporal_load((const f32x4 *)(base + i));
+                x[u] = make_float4(v[0], v[1], v[2], v[3]);
+            }
         }
 #pragma unroll
         for (int u = 0; u < NL; ++u) {

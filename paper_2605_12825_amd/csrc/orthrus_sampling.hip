@@ -17,6 +17,8 @@
 
 namespace orthrus {
 
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
 constexpr int kSChunk = 8192;
 constexpr int kSInlineLayers = 2;
 
@@ -45,7 +47,12 @@ __global__ void __launch_bounds__(256) lse_partial_kernel(const SamplingArgs a)
         for (int u = 0; u < PER / 4; ++u) {
             const int i = begin + (u * 256 + tid) * 4;
             float4 vp = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY), vq = vp;
-            if (i < end) { vp = *(const float4 *)(pr + i); vq = *(const float4 *)(qr + i); }
+            if (i < end) {  // one pass over both logit sets: loads that do not displace anything in the caches
+                const f32x4 tp = __builtin_nontemporal_load((const f32x4 *)(pr + i));
+                const f32x4 tq = __builtin_nontemporal_load((const f32x4 *)(qr + i));
+                vp = make_float4(tp[0], tp[1], tp[2], tp[3]);
+                vq = make_float4(tq[0], tq[1], tq[2], tq[3]);
+            }
             xp[4 * u] = vp.x; xp[4 * u + 1] = vp.y; xp[4 * u + 2] = vp.z; xp[4 * u + 3] = vp.w;
             xq[4 * u] = vq.x; xq[4 * u + 1] = vq.y; xq[4 * u + 2] = vq.z; xq[4 * u + 3] = vq.w;
         }
