@@ -28,9 +28,9 @@ N_SETS = 4              # rotating sets of block inputs / logits (fresh data eve
 # HBM bytes per attn_split_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (counters scaled by what they read for a plain 1 GiB copy; see profiles/), keyed by
 # (workload, splits): reads + writes of that kernel.
-MEASURED_TRAFFIC_BYTES = {("long", 8): int((539.07 + 8.52) * 1e6),
+MEASURED_TRAFFIC_BYTES = {("long", 8): int((539.08 + 8.52) * 1e6),
                           ("stress", 1): int((557.39 + 8.39) * 1e6),
-                          ("mixed", 0): int((163.53 + 38.86) * 1e6)}   # balanced partition
+                          ("mixed", 0): int((163.48 + 38.89) * 1e6)}   # balanced partition
 
 
 def log(*a):
