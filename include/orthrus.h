@@ -82,7 +82,10 @@ typedef struct {
     int32_t max_seq_len;       /* HOST upper bound on every seq_lens[b] during the call (sizes the grid) */
     int32_t num_splits;        /* attention: KV splits per (sequence, KV head); 0 = library chooses;
                                   ORTHRUS_SPLITS_BALANCED = even partition of the whole batch (below) */
-    int32_t num_layers;        /* commit: layers written per call (block K/V and pools carry a layer axis) */
+    int32_t num_layers;        /* layers of the model.  commit: layers written per call (block K/V and pools
+                                  carry a layer axis).  attention: how many caches of this size the model
+                                  streams between two passes over the same layer (with batch and max_seq_len
+                                  it decides whether the K/V loads bypass the caches); <= 1 counts as 1 */
     int32_t vocab;             /* consensus: V */
     float sm_scale;            /* score scale of Eq. 4, normally 1/sqrt(d) */
     int64_t num_pages;         /* pages in each pool; page ids outside [0, num_pages) count as unmapped */

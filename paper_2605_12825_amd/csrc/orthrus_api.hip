@@ -77,7 +77,7 @@ orthrus_status check_params(const orthrus_params *p, bool need_attn, bool need_c
 orthrus_status make_plan(const orthrus_params *p, int num_cus, orthrus::AttnPlan *plan)
 {
     orthrus::plan_attn(p->head_dim, p->num_q_heads / p->num_kv_heads, p->block_k, p->batch, p->num_kv_heads,
-                       p->max_seq_len, p->num_splits, num_cus, plan);
+                       p->max_seq_len, p->num_splits, num_cus, p->num_layers, plan);
     if (plan->num_splits > 65535 * 16) return ORTHRUS_EUNSUPPORTED;
     // the balanced partition counts one head's tiles in a 32-bit int
     if (plan->bal_wgs > 0 && (int64_t)p->batch * (p->max_seq_len / 32 + 2) > 0x7fffffff) return ORTHRUS_EUNSUPPORTED;

@@ -761,7 +761,7 @@ static size_t lds_need(int head_dim)
 }
 
 hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv_heads, int max_seq_len,
-                     int requested_splits, int num_cus, AttnPlan *plan)
+                     int requested_splits, int num_cus, int num_layers, AttnPlan *plan)
 {
     const int R = group * block_k;
     plan->rows = R;
@@ -776,8 +776,10 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     if (per_cu > 12 / (W + 1)) per_cu = 12 / (W + 1);
     if (per_cu < 1) per_cu = 1;
     plan->bal_wgs = 0;
-    // K/V bytes one call streams at most, against the 256 MB last-level cache (see the kernel's loads)
-    plan->kv_nt = (double)batch * max_seq_len * num_kv_heads * 4.0 * head_dim > 1.25 * 256.0 * 1024 * 1024 ? 1 : 0;
+    // K/V bytes the model streams at most between two passes over the same layer's cache (the other
+    // layers' caches come in between), against the 256 MB last-level cache (see the kernel's loads)
+    const double stream_bytes = (double)(num_layers > 1 ? num_layers : 1) * batch * max_seq_len * num_kv_heads * 4.0 * head_dim;
+    plan->kv_nt = stream_bytes > 1.25 * 256.0 * 1024 * 1024 ? 1 : 0;
     if (requested_splits < 0) {
         // balanced partition: as many workgroups as are resident at once, two partial slots each
         plan->bal_wgs = num_cus * per_cu;

@@ -77,7 +77,7 @@ struct AttnLaunchEvents {
 
 // Host-side launchers (defined next to the kernels).  Return hipSuccess or the launch error.
 hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv_heads, int max_seq_len,
-                     int requested_splits, int num_cus, AttnPlan *plan);
+                     int requested_splits, int num_cus, int num_layers, AttnPlan *plan);
 hipError_t launch_attn(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream,
                        AttnLaunchEvents *events = nullptr);
 hipError_t launch_prefill_attn(const AttnArgs &a, int head_dim, hipStream_t stream);
