@@ -25,6 +25,12 @@
 //            split 0.  A wave owns its rows outright, so there is no merge inside the workgroup:
 //            it writes final bf16 rows (one split) or an fp32 partial in register order that
 //            attn_combine_kernel merges in a fixed split order (deterministic).
+//   other forms of the same kernel: the balanced partition of a ragged batch's tiles over the
+//            resident workgroups (template flag BALANCED) and the AR view's causal prefill (PREFILL);
+//            both are described at the kernel.
+//   caches = K/V tiles are read once per call.  When the model streams more K/V between two passes
+//            over the same cache than the last-level cache holds, the tile loads carry the
+//            non-temporal hint; the fp32 partials always leave with non-temporal stores.
 #include "orthrus_internal.h"
 
 #include <hip/hip_ext.h>
