@@ -231,19 +231,40 @@ def test_long_config_attention_sampled_head(splits):
         _check_attn(got[b:b + 1, :, g * G:(g + 1) * G], want, "long view %d splits %d" % (view, splits))
 
 
-def test_bad_page_is_flagged_not_dereferenced():
+@pytest.mark.parametrize("splits", [0, -1])
+def test_bad_page_is_flagged_not_dereferenced(splits):
     w = Workload(name="badpg", batch=2, num_q_heads=4, num_kv_heads=2, head_dim=128, block_k=4, context=100,
                  page_size=16, seed=9)
     cache = make_cache(w)
     cache["page_table"][1, 2] = 10 ** 6
     cache["page_table"][1, 3] = -1
-    case = GpuCase(w, cache)
+    case = GpuCase(w, cache, num_splits=splits)
     blk = make_block(w, 10)
     got = case.attn(AR, blk, want_lse=False)
     assert case.step.device_error() == -4
     assert case.step.device_error() == 0                      # reading clears the flag
     sb, sc = _sub_batch(blk, cache, [0])
     _check_attn(got[:1], _oracle_attn(AR, w, sb, sc), "unaffected sequence")
+
+
+@pytest.mark.parametrize("splits", [0, 3, -1])
+def test_length_beyond_the_host_bound_is_flagged_and_clamped(splits):
+    """seq_lens[b] outside [0, max_seq_len]: the error word is set, the length is clamped (no read past the
+    mapped pages), and the other sequences are unaffected."""
+    w = Workload(name="badlen", batch=3, num_q_heads=8, num_kv_heads=2, head_dim=128, block_k=8, context=200,
+                 page_size=16, seed=19)
+    cache = make_cache(w, seq_lens=np.array([200, 200, 90], np.int32))   # pages mapped for the clamped lengths
+    case = GpuCase(w, cache, num_splits=splits, max_seq_len=200)
+    case.seq_lens.copy_(_dev(np.array([200, 100000, -5], np.int32)))
+    blk = make_block(w, 20)
+    got = case.attn(DIFF, blk, want_lse=False)
+    assert case.step.device_error() == -4
+    assert np.all(np.isfinite(got))
+    sb, sc = _sub_batch(blk, cache, [0])
+    _check_attn(got[:1], _oracle_attn(DIFF, w, sb, sc), "unaffected sequence")
+    # the clamped sequences behave as lengths 200 and 0
+    clamped = dict(cache, seq_lens=np.array([200, 200, 0], np.int32))
+    _check_attn(got, _oracle_attn(DIFF, w, blk, clamped), "clamped lengths")
 
 
 # --------------------------------------------------------------------------------------------- consensus
