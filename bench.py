@@ -53,6 +53,8 @@ def parse():
                     help="> 1 (or --graph): time whole decode cycles over a stack of layers: the diffusion pass "
                          "through every layer, the AR pass through every layer, consensus + commit into all of them")
     ap.add_argument("--graph", action="store_true", help="replay each cycle as one HIP graph instead of eager launches")
+    ap.add_argument("--diffusion-passes", type=int, default=1,
+                    help="with --layers/--graph: diffusion-view passes per cycle (2 = the paper's multi-step ablation)")
     ap.add_argument("--block-k", type=int, default=0, help="override the workload's block size K (latency-vs-K sweeps)")
     ap.add_argument("--prefill", type=int, default=0,
                     help="> 0: time orthrus_prefill_attn (AR prefill of one layer) for that many new tokens per "
@@ -245,7 +247,7 @@ def run_stack(args, torch, rt, w, cache, host_sets, cons_sets, splits):
         st = rt.DecodeStack(num_layers=nl, batch=B, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
                             head_dim=w.head_dim, block_k=K, page_size=w.page_size, k_pool=k_pool, v_pool=v_pool,
                             page_table=page_table, seq_lens=seq_lens, max_seq_len=cap, vocab=w.vocab,
-                            num_splits=splits, temperature=T)
+                            num_splits=splits, temperature=T, diffusion_passes=args.diffusion_passes)
         d, a = host_sets[i]
         for name, blk, key in (("q_diff", d, "q"), ("k_blk_diff", d, "k_blk"), ("v_blk_diff", d, "v_blk"),
                                ("q_ar", a, "q"), ("k_blk_ar", a, "k_blk"), ("v_blk_ar", a, "v_blk")):
@@ -286,7 +288,8 @@ def run_stack(args, torch, rt, w, cache, host_sets, cons_sets, splits):
     mean_tokens = 0.5 * (lens_before.sum() + lens_after.sum())
     kv_bytes = mean_tokens * w.num_kv_heads * 2 * w.head_dim * 2          # one attention call
     committed = float((lens_after - lens_before).sum()) / args.steps       # tokens per cycle, whole batch
-    whole = 2 * nl * kv_bytes / (ms * 1e-3) / 1e9
+    passes = args.diffusion_passes + 1   # forward passes per cycle: the diffusion view's, then the AR view's
+    whole = passes * nl * kv_bytes / (ms * 1e-3) / 1e9
     out = {
         "metric": "draft+verify block-attn steps/s and achieved KV-read HBM TB/s (1 MI355X)",
         "value": round(1000.0 / ms, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -296,16 +299,17 @@ def run_stack(args, torch, rt, w, cache, host_sets, cons_sets, splits):
                    "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim, "block_k": K,
                    "context": int(lens_before.max()), "page_size": w.page_size, "vocab": w.vocab,
                    "num_splits": stacks[0].step.num_splits, "layers": nl, "graph": bool(args.graph), "temperature": T,
+                   "diffusion_passes": args.diffusion_passes,
                    "step": "one decode cycle: %d diffusion attn + %d AR verify attn + consensus + commit into "
-                           "%d layers" % (nl, nl, nl)},
+                           "%d layers" % (nl * args.diffusion_passes, nl, nl)},
         "roofline": {"bound": "hbm", "achieved": round(whole, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(whole / HBM_PEAK_GBS, 4), "traffic": None,
                      "kernel": "whole cycle (all attention launches + consensus + commit), not one kernel: "
-                               "algorithmic KV bytes of the %d attention calls over the cycle time" % (2 * nl),
-                     "avg_launch_us": round(ms * 1e3 / (2 * nl), 2), "algorithmic_bytes_per_launch": int(kv_bytes)},
+                               "algorithmic KV bytes of the %d attention calls over the cycle time" % (passes * nl),
+                     "avg_launch_us": round(ms * 1e3 / (passes * nl), 2), "algorithmic_bytes_per_launch": int(kv_bytes)},
         "detail": {"tokens_per_s": round(committed / (ms * 1e-3), 1),
                    "tokens_committed_per_cycle_per_sequence": round(committed / max(B, 1), 3),
-                   "tokens_per_forward_pass": round(committed / max(B, 1) / 2.0, 3),
+                   "tokens_per_forward_pass": round(committed / max(B, 1) / passes, 3),
                    "cycle_us_per_layer": round(ms * 1e3 / nl, 2)},
     }
     for st in stacks:

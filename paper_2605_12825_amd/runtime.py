@@ -131,11 +131,17 @@ class DecodeStack:
 
     def __init__(self, *, num_layers, batch, num_q_heads, num_kv_heads, head_dim, block_k, page_size,
                  k_pool, v_pool, page_table, seq_lens, max_seq_len, vocab, num_splits=0, temperature=0.0,
-                 device=0):
+                 diffusion_passes=1, device=0):
         if k_pool.dim() != 5 or k_pool.shape[0] != num_layers or not k_pool.is_contiguous():
             raise ValueError("pools must be contiguous [layers, pages, H_kv, P, d]")
         L, pages, H, P, d = k_pool.shape
         self.num_layers, self.temperature = num_layers, float(temperature)
+        # forward passes of the diffusion view per cycle: 1 is the paper's single-step projection, 2 the
+        # multi-step denoising variant of its ablation (Section 4.4, Table 5); the passes run back to back
+        # over the same buffers (whatever refines the block between them writes q_diff / k_blk_diff / v_blk_diff)
+        self.diffusion_passes = int(diffusion_passes)
+        if self.diffusion_passes < 1:
+            raise ValueError("diffusion_passes must be >= 1")
         self.k_pool, self.v_pool, self.page_table, self.seq_lens = k_pool, v_pool, page_table, seq_lens
         self.step = DecodeStep(batch=batch, num_q_heads=num_q_heads, num_kv_heads=num_kv_heads, head_dim=head_dim,
                                block_k=block_k, page_size=page_size, max_pages_per_seq=page_table.shape[1],
@@ -165,8 +171,9 @@ class DecodeStack:
     def cycle(self, stream=None) -> None:
         """Issues the whole cycle on `stream` (default: the current stream)."""
         s = self.step
-        for view, q, kb, vb, out in ((0, self.q_diff, self.k_blk_diff, self.v_blk_diff, self.out_diff),
-                                     (1, self.q_ar, self.k_blk_ar, self.v_blk_ar, self.out_ar)):
+        diff = (0, self.q_diff, self.k_blk_diff, self.v_blk_diff, self.out_diff)
+        ar = (1, self.q_ar, self.k_blk_ar, self.v_blk_ar, self.out_ar)
+        for view, q, kb, vb, out in (diff,) * self.diffusion_passes + (ar,):
             for l in range(self.num_layers):
                 s.attn(view, q[l], kb[l], vb[l], self.k_pool[l], self.v_pool[l], self.page_table, self.seq_lens,
                        out[l], None, stream)

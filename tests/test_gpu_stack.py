@@ -142,6 +142,34 @@ def test_stack_sampling_cycle_graph_replay_matches_eager():
     graph.close()
 
 
+def test_two_diffusion_passes_per_cycle_leave_the_results_unchanged():
+    """The multi-step variant of the paper's ablation (Section 4.4) runs the diffusion view twice per cycle;
+    over unchanged inputs the second pass reproduces the first, eagerly and in a replayed graph."""
+    w = _workload()
+    kp, vp, pt, lens = _initial_state(w)
+    one = _make_stack(w, kp, vp, pt, lens)
+    two = _make_stack(w, kp, vp, pt, lens, diffusion_passes=2)
+    two_g = _make_stack(w, kp, vp, pt, lens, diffusion_passes=2)
+    two_g.capture()
+    for c in range(2):
+        inp = _cycle_inputs(w, c)
+        snaps = []
+        for st in (one, two):
+            _upload(st, inp)
+            st.cycle()
+            snaps.append(_snapshot(st))
+        _upload(two_g, inp)
+        torch.cuda.synchronize()
+        two_g.replay()
+        two_g.graph_stream.synchronize()
+        snaps.append(_snapshot(two_g))
+        for other in snaps[1:]:
+            for n in snaps[0]:
+                np.testing.assert_array_equal(snaps[0][n], other[n], err_msg="%s cycle %d" % (n, c))
+    for st in (one, two, two_g):
+        st.close()
+
+
 def test_graph_begin_rejects_null_stream_and_timing():
     from paper_2605_12825_amd import binding as B
     w = _workload()
