@@ -27,10 +27,11 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E published peak
 N_SETS = 4              # rotating sets of block inputs / logits (fresh data every step, cycled)
 # HBM bytes per attn_split_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (counters scaled by what they read for a plain 1 GiB copy; see profiles/), keyed by
-# (workload, splits): reads + writes of that kernel.
-MEASURED_TRAFFIC_BYTES = {("long", 8): int((539.08 + 8.52) * 1e6),
-                          ("stress", 1): int((557.39 + 8.39) * 1e6),
-                          ("mixed", 0): int((163.48 + 38.89) * 1e6)}   # balanced partition
+# (workload, splits, block size K): reads + writes of that kernel.
+MEASURED_TRAFFIC_BYTES = {("long", 8, 16): int((539.08 + 8.52) * 1e6),
+                          ("long", 8, 32): int((540.36 + 17.05) * 1e6),
+                          ("stress", 1, 16): int((557.39 + 8.39) * 1e6),
+                          ("mixed", 0, 32): int((163.48 + 38.89) * 1e6)}   # balanced partition
 
 
 def log(*a):
@@ -472,7 +473,7 @@ def main():
         call_gbs = kv_bytes / ((split_avg + comb_avg) * 1e-6) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, step.num_splits)),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, step.num_splits, K)),
                     "kernel": "attn_split_kernel",
                     "events": "HIP events attached to the kernel's own dispatches in every %d-th timed step "
                               "(%d launches)" % (args.event_every, split_n),
