@@ -25,13 +25,25 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E published peak
 N_SETS = 4              # rotating sets of block inputs / logits (fresh data every step, cycled)
-# HBM bytes per attn_split_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script (counters scaled by what they read for a plain 1 GiB copy; see profiles/), keyed by
-# (workload, splits, block size K): reads + writes of that kernel.
-MEASURED_TRAFFIC_BYTES = {("long", 8, 16): int((539.08 + 8.52) * 1e6),
-                          ("long", 8, 32): int((540.36 + 17.05) * 1e6),
-                          ("stress", 1, 16): int((557.39 + 8.39) * 1e6),
-                          ("mixed", 0, 32): int((163.48 + 38.89) * 1e6)}   # balanced partition
+
+
+def measured_traffic(workload, block_k, splits):
+    """HBM bytes per attention call from the rocprofv3 --pmc summary committed for this very configuration.
+
+    A summary under profiles/ that was made from FETCH_SIZE / WRITE_SIZE runs of this script carries a line
+    `traffic-per-call: workload=<w> block_k=<K> splits=<S> read_bytes=<n> write_bytes=<n>` (counters scaled by
+    what they read for a plain copy of known size).  No such line for the configuration at hand: null.
+    """
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        for line in open(path):
+            m = re.match(r"\s*traffic-per-call: workload=(\S+) block_k=(\d+) splits=(\S+) read_bytes=(\d+) "
+                         r"write_bytes=(\d+)", line)
+            if m and m.group(1) == workload and int(m.group(2)) == block_k and m.group(3) == str(splits):
+                return {"traffic": int(m.group(4)) + int(m.group(5)),
+                        "traffic_source": os.path.relpath(path, ROOT)}
+    return {"traffic": None, "traffic_source": None}
 
 
 def log(*a):
@@ -65,12 +77,37 @@ def parse():
                          "sequences of 2048 tokens with 256 anchor blocks of K=32 each (the paper's training "
                          "geometry), with the workload's head shapes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--event-every", type=int, default=8,
-                    help="time the kernels of every Nth timed step with HIP events (0: never)")
+    ap.add_argument("--prewarm-ms", type=float, default=600.0,
+                    help="untimed attention-only steps issued for this long before the warm-up steps, so that the "
+                         "GPU clocks have settled when the timed region starts")
+    ap.add_argument("--kernel-steps", type=int, default=48,
+                    help="whole steps run after the timed region with HIP events attached to the attention "
+                         "kernels (two attention calls each; 0: no kernel timing, no roofline)")
+    ap.add_argument("--kernel-every", type=int, default=1,
+                    help="attach the events to every Nth of those steps only")
+    ap.add_argument("--ceiling-launches", type=int, default=50,
+                    help="launches of the no-arithmetic K/V stream probe that measure the ceiling")
+    ap.add_argument("--pools", type=int, default=0,
+                    help="copies of the cache to rotate over (0: 4 for a workload without a commit step, else 1)")
+    ap.add_argument("--calibrate-read", action="store_true",
+                    help="only time the no-arithmetic K/V stream probe on the workload's cache (the measured "
+                         "ceiling of the paged read pattern) and print it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (known traffic, used to "
                          "scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
+
+
+def settle_clocks(torch, ms, one):
+    """Issues `one()` (a state-preserving launch sequence) for about `ms` milliseconds, untimed: after idle the
+    GPU needs tens of milliseconds of load before its clocks reach their steady state."""
+    t0, n = time.perf_counter(), 0
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(10):
+            one()
+            n += 1
+        torch.cuda.synchronize()
+    return n
 
 
 def cpu_baseline(w, cache, host_sets, cons_sets):
@@ -133,6 +170,7 @@ def run_prefill(args, torch, rt, w):
     def one():
         seq_lens.copy_(zero)   # every timed call prefills the same empty cache again
         step.prefill(T, q, kn, vn, new_lens, k_pool, v_pool, page_table, seq_lens, out)
+    settle_clocks(torch, args.prewarm_ms, one)
     for _ in range(args.warmup):
         one()
     torch.cuda.synchronize()
@@ -201,6 +239,7 @@ def run_train_mask(args, torch, rt, w, splits):
     pt, sl = D(np.ascontiguousarray(page_table)), D(anchors.reshape(-1))
     stream = torch.cuda.current_stream()
     one = lambda: step.attn(0, q, kd, vd, k_ar, v_ar, pt, sl, out)
+    settle_clocks(torch, args.prewarm_ms, one)
     for _ in range(args.warmup):
         one()
     torch.cuda.synchronize()
@@ -269,6 +308,11 @@ def run_stack(args, torch, rt, w, cache, host_sets, cons_sets, splits):
                 st.replay(stream)
             else:
                 st.cycle(stream)
+        st0 = stacks[0]
+        settle_clocks(torch, args.prewarm_ms,
+                      lambda: st0.step.attn(0, st0.q_diff[0], st0.k_blk_diff[0], st0.v_blk_diff[0], st0.k_pool[0],
+                                            st0.v_pool[0], st0.page_table, st0.seq_lens, st0.out_diff[0], None,
+                                            stream))
         for i in range(args.warmup):
             run(i)
         stream.synchronize()
@@ -345,7 +389,7 @@ def main():
     if args.block_k > 0:
         w = w.with_(block_k=args.block_k)
     # capacity: the cache grows by <= K tokens per committed step (never, for a workload without consensus)
-    w = w.with_(steps=(total_steps + 1) if w.vocab else 0)
+    w = w.with_(steps=(total_steps + args.kernel_steps + 1) if w.vocab else 0)
     if args.paging:
         w = w.with_(paging=args.paging)
     splits = {"workload": w.num_splits, "balanced": -1}.get(args.num_splits)
@@ -380,7 +424,17 @@ def main():
 
     dev = torch.device("cuda:0")
     D = rt.to_device_bits
-    k_pool, v_pool = D(cache["k_pool"]), D(cache["v_pool"])
+    # Workloads without a commit step may rotate over several copies of the cache, so that the last-level
+    # cache (256 MB) cannot serve a pass from what the previous one left there.
+    n_pools = args.pools if args.pools > 0 else (4 if not w.vocab else 1)
+    if w.vocab and n_pools > 1:
+        log("bench.py: --pools needs a workload without a commit step (the commit writes one cache)")
+        sys.exit(2)
+    k_pools, v_pools = [D(cache["k_pool"])], [D(cache["v_pool"])]
+    for _ in range(1, n_pools):
+        k_pools.append(k_pools[0].clone())
+        v_pools.append(v_pools[0].clone())
+    k_pool, v_pool = k_pools[0], v_pools[0]
     page_table, seq_lens = D(cache["page_table"]), D(cache["seq_lens"])
     sets = [tuple({k: D(v) for k, v in blk.items()} for blk in pair) for pair in host_sets]
     csets = [{k: D(v) for k, v in c.items() if isinstance(v, np.ndarray) and not k.startswith("planted")}
@@ -392,31 +446,32 @@ def main():
     toks = torch.empty((B, K), dtype=torch.int32, device=dev)
     len0 = int(cache["seq_lens"].max())
     cap = min(w.capacity_tokens(), cache["page_table"].shape[1] * w.page_size)
-    step = rt.DecodeStep(batch=B, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
-                         block_k=K, page_size=w.page_size, max_pages_per_seq=cache["page_table"].shape[1],
-                         max_seq_len=cap, num_pages=cache["num_pages"], vocab=w.vocab,
-                         num_splits=splits, min_seq_len_bound=len0)
+    mk_step = lambda ns: rt.DecodeStep(batch=B, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
+                                       head_dim=w.head_dim, block_k=K, page_size=w.page_size,
+                                       max_pages_per_seq=cache["page_table"].shape[1], max_seq_len=cap,
+                                       num_pages=cache["num_pages"], vocab=w.vocab, num_splits=ns,
+                                       min_seq_len_bound=len0)
+    step = mk_step(splits)
     stream = torch.cuda.current_stream()
     call_events = []
 
-    def run_step(i, record):
+    def attn_pair(st, i):
+        d, a = sets[i % N_SETS]
+        kp, vp = k_pools[i % n_pools], v_pools[i % n_pools]
+        st.attn(0, d["q"], d["k_blk"], d["v_blk"], kp, vp, page_table, seq_lens, o_d)
+        st.attn(1, a["q"], a["k_blk"], a["v_blk"], kp, vp, page_table, seq_lens, o_a)
+
+    def run_step(i, record=False):
         # the host's own upper bound on the lengths: initial maximum plus K tokens per step so far
         # (no device round trip); it sizes the attention grid of this step
         step.set_max_seq_len(min(cap, len0 + (i if w.vocab else 0) * K))
-        d, a = sets[i % N_SETS]
-        # sampled steps: the library attaches HIP events to its attention kernels' own dispatches
-        # (kernel execution time, no marker between kernels); the consensus call sits between two
-        # ordinary events on the same stream
-        step.attn_timing(record)
-        step.attn(0, d["q"], d["k_blk"], d["v_blk"], k_pool, v_pool, page_table, seq_lens, o_d)
-        step.attn(1, a["q"], a["k_blk"], a["v_blk"], k_pool, v_pool, page_table, seq_lens, o_a)
-        if record:
-            step.attn_timing(False)
+        attn_pair(step, i)
         if w.vocab:
             ev = None
             if record:
                 ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
                 ev[0].record(stream)
+            a = sets[i % N_SETS][1]
             cs = csets[i % N_SETS]
             if T > 0:
                 step.sampling_consensus_commit(T, cs["ar_logits"], cs["diff_logits"], cs["draft_tokens"],
@@ -429,30 +484,62 @@ def main():
                 ev[1].record(stream)
                 call_events.append(ev)
 
-    for i in range(args.warmup):
-        run_step(i, False)
-    if args.event_every > 0:
-        # let the library create the events the sampled steps will need now, outside the timed region
-        # (it recycles them after a read); these untimed calls leave the cache as it is
+    # ---- clock settling (untimed, changes no state): after idle the GPU needs tens of milliseconds of
+    # load before its clocks reach their steady state (the first launches run up to 30 % slower), and a
+    # decode loop runs for seconds; so the attention calls of this workload are issued for a while first
+    step.set_max_seq_len(min(cap, len0))
+    pre_i = [0]
+
+    def pre_one():
+        attn_pair(step, pre_i[0])
+        pre_i[0] += 1
+    n_pre = settle_clocks(torch, args.prewarm_ms, pre_one)
+    if args.calibrate_read:
         step.attn_timing(True)
-        step.set_max_seq_len(min(cap, len0 + (args.warmup if w.vocab else 0) * K))
-        d, a = sets[0]
-        for _ in range((args.steps + args.event_every - 1) // args.event_every):
-            step.attn(0, d["q"], d["k_blk"], d["v_blk"], k_pool, v_pool, page_table, seq_lens, o_d)
-            step.attn(1, a["q"], a["k_blk"], a["v_blk"], k_pool, v_pool, page_table, seq_lens, o_a)
+        for j in range(max(args.ceiling_launches, 1)):
+            step.kv_stream_probe(k_pools[j % n_pools], v_pools[j % n_pools], page_table, seq_lens)
         step.attn_timing(False)
-        step.attn_timing_read()
+        torch.cuda.synchronize()
+        pr = np.array([x[0] for x in step.attn_timing_samples()])
+        nbytes = float(cache["seq_lens"].astype(np.int64).sum()) * w.num_kv_heads * 2 * w.head_dim * 2
+        print(json.dumps({"calibrate_read": "the attention kernel with idle compute waves: the K/V loads of one attention "
+                          "call over the %s cache, no arithmetic" % w.name, "bytes_per_launch": int(nbytes),
+                          "launches": int(len(pr)), "avg_us": round(float(pr.mean()), 2),
+                          "median_us": round(float(np.median(pr)), 2), "min_us": round(float(pr.min()), 2),
+                          "max_us": round(float(pr.max()), 2),
+                          "gbs": round(nbytes / (pr.mean() * 1e-6) / 1e9, 1),
+                          "frac_of_peak": round(nbytes / (pr.mean() * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}), flush=True)
+        step.close()
+        return
+    # ---- W warm-up steps, then exactly K timed steps
+    for i in range(args.warmup):
+        run_step(i)
     torch.cuda.synchronize()
     lens_before = seq_lens.cpu().numpy().astype(np.int64)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record(stream)
     for i in range(args.steps):
-        run_step(args.warmup + i, args.event_every > 0 and i % args.event_every == 0)
+        run_step(args.warmup + i)
     e1.record(stream)
     torch.cuda.synchronize()
     total_ms = e0.elapsed_time(e1)
     lens_after = seq_lens.cpu().numpy().astype(np.int64)
+
+    # ---- kernel timing block (after the timed region, same stream, same state evolution): more whole
+    # steps, now with HIP events attached to the attention kernels' own dispatches (kernel execution
+    # time, no marker between kernels) and ordinary events around the consensus call
+    n_post = args.kernel_steps
+    samples = []
+    if n_post > 0:
+        for j in range(n_post):
+            rec = j % args.kernel_every == 0
+            step.attn_timing(rec)
+            run_step(total_steps + j, record=rec)
+        step.attn_timing(False)
+        torch.cuda.synchronize()
+        samples = step.attn_timing_samples()
+    lens_post = seq_lens.cpu().numpy().astype(np.int64)
     err = step.device_error()
     if err != 0:
         log("bench.py: device error word %d after the timed region" % err)
@@ -460,29 +547,81 @@ def main():
 
     ms_per_step = total_ms / args.steps
     # algorithmic KV bytes of one attention launch: 2*d*2 bytes per cached token per KV head,
-    # at the mean cached length over the timed steps
-    mean_tokens = 0.5 * (lens_before.sum() + lens_after.sum())
-    kv_bytes = mean_tokens * w.num_kv_heads * 2 * w.head_dim * 2
+    # at the mean cached length over the steps in question
+    row_bytes = w.num_kv_heads * 2 * w.head_dim * 2
+    kv_bytes = 0.5 * (lens_before.sum() + lens_after.sum()) * row_bytes
+    kv_bytes_post = 0.5 * (lens_after.sum() + lens_post.sum()) * row_bytes
+    R = w.group * K
+
+    def stats(us):
+        us = np.asarray(us, dtype=np.float64)
+        return {"avg_us": round(float(us.mean()), 2), "median_us": round(float(np.median(us)), 2),
+                "min_us": round(float(us.min()), 2), "max_us": round(float(us.max()), 2)}
+
+    def rates(us_mean, nbytes):
+        gbs = nbytes / (us_mean * 1e-6) / 1e9
+        return {"achieved": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
     roofline = None
     extra = {}
-    split_us, split_n, comb_us, comb_n = step.attn_timing_read()
-    if split_n:
-        split_avg = split_us / split_n
-        comb_avg = comb_us / comb_n if comb_n else 0.0
-        achieved = kv_bytes / (split_avg * 1e-6) / 1e9
-        call_gbs = kv_bytes / ((split_avg + comb_avg) * 1e-6) / 1e9
-        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, step.num_splits, K)),
-                    "kernel": "attn_split_kernel",
-                    "events": "HIP events attached to the kernel's own dispatches in every %d-th timed step "
-                              "(%d launches)" % (args.event_every, split_n),
-                    "avg_launch_us": round(split_avg, 2), "algorithmic_bytes_per_launch": int(kv_bytes)}
-        extra["attn_split_kernel_us"] = round(split_avg, 2)
-        extra["attn_combine_kernel_us"] = round(comb_avg, 2)
-        extra["attn_call_kernels_us"] = round(split_avg + comb_avg, 2)
-        extra["attn_call_kv_gbs"] = round(call_gbs, 1)
-        extra["attn_call_frac_of_peak"] = round(call_gbs / HBM_PEAK_GBS, 4)
+    if samples:
+        sp = np.array([x[0] for x in samples])
+        cb = np.array([x[1] for x in samples])
+        call = sp + cb
+        r_call, r_split = rates(call.mean(), kv_bytes_post), rates(sp.mean(), kv_bytes_post)
+        tf = kv_bytes_post * R / (call.mean() * 1e-6) / 1e12     # R flop per K/V byte: 4 R d flop per 4 d bytes
+        roofline = {"bound": "hbm", "achieved": r_call["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": r_call["frac"],
+                    "kernel": "one orthrus_dual_view_attn call = attn_split_kernel" +
+                              (" + attn_combine_kernel" if cb.max() > 0 else "") +
+                              " (the call, not the split kernel alone, is what the fraction is of)",
+                    "launches": int(len(samples)),
+                    "events": "HIP events attached to the kernels' own dispatches in %d whole steps that follow "
+                              "the timed region on the same stream" % n_post,
+                    "avg_launch_us": stats(call)["avg_us"], "launch_us": stats(call),
+                    "algorithmic_bytes_per_launch": int(kv_bytes_post),
+                    "split_kernel": dict(stats(sp), **r_split),
+                    "combine_kernel": stats(cb) if cb.max() > 0 else None,
+                    "mfma": {"flop_per_byte": R, "achieved_tflops": round(tf, 1), "peak_tflops": 2500.0,
+                             "frac": round(tf / 2500.0, 4)}}
+        roofline.update(measured_traffic(w.name, K, "balanced" if splits == -1 else step.num_splits))
+        extra["attn_split_kernel_us"] = stats(sp)["avg_us"]
+        extra["attn_combine_kernel_us"] = stats(cb)["avg_us"]
+        extra["attn_call_kernels_us"] = stats(call)["avg_us"]
+        extra["attn_call_frac_of_peak"] = r_call["frac"]
+        # ---- measured ceiling of the access pattern: the same bytes through the same page table, no arithmetic
+        step.attn_timing(True)
+        for j in range(args.ceiling_launches):
+            step.kv_stream_probe(k_pools[j % n_pools], v_pools[j % n_pools], page_table, seq_lens)
+        step.attn_timing(False)
+        torch.cuda.synchronize()
+        pr = np.array([x[0] for x in step.attn_timing_samples()])
+        if len(pr):
+            kv_now = lens_post.sum() * row_bytes
+            c = rates(pr.mean(), kv_now)
+            roofline["ceiling"] = dict(stats(pr), kernel="the attention kernel with idle compute waves (same grid, same "
+                                       "K/V loads through the page table, no arithmetic)", launches=int(len(pr)),
+                                       achieved=c["achieved"], frac_of_peak=c["frac"])
+            roofline["ceiling_frac"] = round(r_call["achieved"] / c["achieved"], 4)
+        # ---- the long workload names 64 splits per sequence: that plan, timed side by side
+        if w.name == "long" and args.block_k == 0 and step.num_splits != 64:
+            s64 = mk_step(64)
+            s64.set_max_seq_len(min(cap, int(lens_post.max())))
+            for j in range(10):
+                attn_pair(s64, j)
+            s64.attn_timing(True)
+            for j in range(max(8, n_post // 2)):
+                attn_pair(s64, j)
+            s64.attn_timing(False)
+            torch.cuda.synchronize()
+            x = s64.attn_timing_samples()
+            sp64, cb64 = np.array([v[0] for v in x]), np.array([v[1] for v in x])
+            kv_now = lens_post.sum() * row_bytes
+            extra["prescribed_64_splits"] = {"split_kernel": dict(stats(sp64), **rates(sp64.mean(), kv_now)),
+                                             "combine_kernel": stats(cb64),
+                                             "call": dict(stats(sp64 + cb64), **rates((sp64 + cb64).mean(), kv_now)),
+                                             "launches": int(len(x)), "library_choice_splits": step.num_splits}
+            s64.close()
     if call_events:
         c_ms = np.array([ev[0].elapsed_time(ev[1]) for ev in call_events])
         extra["consensus_commit_us"] = round(float(c_ms.mean()) * 1e3, 2)
@@ -490,6 +629,9 @@ def main():
         extra["consensus_logits_gbs"] = round(nlog * B * K * w.vocab * 4 / (float(c_ms.mean()) * 1e-3) / 1e9, 1)
     extra["kv_read_tbs_whole_step"] = round(2 * kv_bytes / (ms_per_step * 1e-3) / 1e12, 3)
     extra["tokens_committed_per_step"] = round(float((lens_after - lens_before).sum()) / args.steps / max(B, 1), 3)
+    extra["prewarm"] = "%d untimed attention-only steps over %.0f ms before the warm-up steps (clock settling)" % (
+        n_pre, args.prewarm_ms)
+    extra["pools"] = n_pools
 
     out = {
         "metric": "draft+verify block-attn steps/s and achieved KV-read HBM TB/s (1 MI355X)",

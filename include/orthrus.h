@@ -116,6 +116,19 @@ int64_t orthrus_sampling_workspace_bytes(const orthrus_params *p);
 /* Number of KV splits the attention call will use for these params (>= 1; 0 for the balanced
    partition, which has no fixed split count), or a negative status. */
 int32_t orthrus_attn_num_splits(const orthrus_params *p);
+/*
+ * The attention launch plan (split count, workgroups of the balanced partition, hence the workspace)
+ * follows the compute-unit count of the context's device.  The two queries above assume the full
+ * 256-CU part; these two answer for the device `ctx` was created on and are the ones to use when that
+ * device exposes fewer CUs (a partitioned GPU).  orthrus_dual_view_attn checks the workspace against
+ * the plan it actually uses and returns ORTHRUS_EWORKSPACE if it is too small.
+ */
+int32_t orthrus_attn_num_splits_on(const orthrus_ctx *ctx, const orthrus_params *p);
+int64_t orthrus_attn_workspace_bytes_on(const orthrus_ctx *ctx, const orthrus_params *p);
+/* Identifier of the sources and compiler flags this library was built from (a hex digest chosen by the
+   build script; "unknown" if built by hand).  Lets a binding detect a library that is older than the
+   sources next to it. */
+const char *orthrus_build_id(void);
 
 /*
  * Block attention of one view over the shared cache — Section 3.1, Eq. 4 of the paper:
@@ -294,6 +307,33 @@ orthrus_status orthrus_graph_destroy(orthrus_graph *graph);
 orthrus_status orthrus_attn_timing(orthrus_ctx *ctx, int enable);
 orthrus_status orthrus_attn_timing_read(orthrus_ctx *ctx, double *split_us, int64_t *split_launches,
                                         double *combine_us, int64_t *combine_launches);
+/*
+ * The same records one by one instead of summed: for the i-th timed call since the last read, in launch
+ * order, split_us[i] is its split kernel's time and combine_us[i] its combine kernel's (0 when the call
+ * had none), both in microseconds.  At most `capacity` entries are written to the two [host] arrays;
+ * *count receives the number of timed calls (it may exceed capacity: the rest are dropped).  Resets the
+ * records like orthrus_attn_timing_read.
+ */
+orthrus_status orthrus_attn_timing_samples(orthrus_ctx *ctx, double *split_us, double *combine_us, int64_t capacity,
+                                          int64_t *count);
+
+/*
+ * Measurement helper: the K/V stream of one attention call with no arithmetic.  Sections 1, 2.1 and 3.1
+ * name the repeated loading of the KV cache as the memory-bandwidth bottleneck of decoding; this call
+ * launches the attention kernel of orthrus_dual_view_attn for these params in a form whose compute
+ * waves do nothing: same grid, same partition of the sequences, the same loads of the cached K and V
+ * rows through the page table, no queries, no arithmetic, nothing written (the block's own K/V tile
+ * is not read either).  Its duration is the time this library's access pattern needs for the call's
+ * K/V bytes on the machine at hand: a measured ceiling to hold the attention kernels against, next to
+ * the published peak.  Asynchronous on `stream`, allocates nothing.  While per-kernel timing is
+ * enabled the launch is recorded like an attention call without a combine kernel.
+ *   k_pool, v_pool, page_table, seq_lens [dev] as in orthrus_dual_view_attn (read only)
+ * Page ids outside [0, num_pages) are read as page 0 and lengths are clamped to [0, max_seq_len], with
+ * the context's error word set as in orthrus_dual_view_attn.
+ */
+orthrus_status orthrus_kv_stream_probe(orthrus_ctx *ctx, const orthrus_params *p, const void *k_pool,
+                                       const void *v_pool, const int32_t *page_table, const int32_t *seq_lens,
+                                       void *stream);
 
 /*
  * Synchronises `stream`, copies the context's device error word to *code [host] (ORTHRUS_OK or

@@ -1,7 +1,7 @@
 """Workload shapes for the dual-view decode step (one attention layer).
 
 The shapes follow the decoding setting of the paper (Section 4.1: Qwen3-class GQA
-models, block size K up to 32, Section 5: contexts up to ~40K tokens) and stand in for
+models, block size K up to 32; Section 4.4, long-context stability: contexts up to ~40K tokens) and stand in for
 its benchmark workloads; every tensor is synthetic and seeded.
 """
 from __future__ import annotations

@@ -29,7 +29,8 @@ EXPORTED = [
     "orthrus_dual_view_attn", "orthrus_consensus_commit", "orthrus_sampling_consensus_commit",
     "orthrus_prefill_workspace_bytes", "orthrus_prefill_attn",
     "orthrus_graph_begin", "orthrus_graph_end", "orthrus_graph_launch", "orthrus_graph_destroy",
-    "orthrus_attn_timing", "orthrus_attn_timing_read", "orthrus_last_device_error",
+    "orthrus_attn_timing", "orthrus_attn_timing_read", "orthrus_attn_timing_samples", "orthrus_last_device_error",
+    "orthrus_attn_num_splits_on", "orthrus_attn_workspace_bytes_on", "orthrus_build_id", "orthrus_kv_stream_probe",
 ]
 
 
@@ -54,8 +55,7 @@ class OrthrusError(RuntimeError):
 
 def _load() -> ctypes.CDLL:
     if not os.path.exists(_build.LIB):
-        # nothing built yet: build once; a stale library is the caller's to rebuild
-        _build.build_library()
+        _build.build_library()   # nothing built yet: build once
     # PyTorch ships its own HIP runtime; load it first so that this library binds to that one.  Two
     # HIP runtimes in one process do not share the GPU: whichever initialises second sees no device.
     try:
@@ -63,6 +63,14 @@ def _load() -> ctypes.CDLL:
     except ImportError:
         pass
     lib = ctypes.CDLL(_build.LIB)
+    # A library older than the sources next to it would silently test yesterday's kernels: its build id is
+    # the digest of the sources and flags it was compiled from, so a mismatch means "rebuild".
+    lib.orthrus_build_id.restype = ctypes.c_char_p
+    lib.orthrus_build_id.argtypes = []
+    built, now = lib.orthrus_build_id().decode(), _build.source_digest()
+    if built != now:
+        raise ImportError("%s was built from other sources (build id %s, sources %s): rebuild it with "
+                          "`python -m paper_2605_12825_amd.build`" % (_build.LIB, built, now))
     vp, i32p = ctypes.c_void_p, ctypes.c_void_p
     pp = ctypes.POINTER(orthrus_params)
     lib.orthrus_create.restype = ctypes.c_int
@@ -108,6 +116,15 @@ def _load() -> ctypes.CDLL:
                                              ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.orthrus_last_device_error.restype = ctypes.c_int
     lib.orthrus_last_device_error.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+    lib.orthrus_attn_timing_samples.restype = ctypes.c_int
+    lib.orthrus_attn_timing_samples.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                                ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
+    lib.orthrus_attn_num_splits_on.restype = ctypes.c_int32
+    lib.orthrus_attn_num_splits_on.argtypes = [vp, pp]
+    lib.orthrus_attn_workspace_bytes_on.restype = ctypes.c_int64
+    lib.orthrus_attn_workspace_bytes_on.argtypes = [vp, pp]
+    lib.orthrus_kv_stream_probe.restype = ctypes.c_int
+    lib.orthrus_kv_stream_probe.argtypes = [vp, pp, vp, vp, i32p, i32p, vp]
     return lib
 
 
@@ -177,6 +194,31 @@ def orthrus_attn_num_splits(p: orthrus_params) -> int:
     if n < 0:
         raise OrthrusError(int(n), "orthrus_attn_num_splits")
     return int(n)
+
+
+def orthrus_attn_num_splits_on(ctx, p: orthrus_params) -> int:
+    n = _lib.orthrus_attn_num_splits_on(ctx, ctypes.byref(p))
+    if n < 0:
+        raise OrthrusError(int(n), "orthrus_attn_num_splits_on")
+    return int(n)
+
+
+def orthrus_attn_workspace_bytes_on(ctx, p: orthrus_params) -> int:
+    n = _lib.orthrus_attn_workspace_bytes_on(ctx, ctypes.byref(p))
+    if n < 0:
+        raise OrthrusError(int(n), "orthrus_attn_workspace_bytes_on")
+    return int(n)
+
+
+def orthrus_build_id() -> str:
+    return _lib.orthrus_build_id().decode()
+
+
+def orthrus_kv_stream_probe(ctx, p: orthrus_params, k_pool, v_pool, page_table, seq_lens, stream=None) -> None:
+    st = _lib.orthrus_kv_stream_probe(ctx, ctypes.byref(p), _ptr(k_pool), _ptr(v_pool), _ptr(page_table),
+                                      _ptr(seq_lens), _stream_handle(stream))
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_kv_stream_probe")
 
 
 def orthrus_dual_view_attn(ctx, p: orthrus_params, view: int, q, k_blk, v_blk, k_pool, v_pool, page_table,
@@ -279,6 +321,18 @@ def orthrus_attn_timing_read(ctx):
     if st != ORTHRUS_OK:
         raise OrthrusError(st, "orthrus_attn_timing_read")
     return su.value, sn.value, cu.value, cn.value
+
+
+def orthrus_attn_timing_samples(ctx, capacity: int = 4096):
+    """Per-call (split kernel us, combine kernel us) of the timed calls since the last read, in launch order."""
+    su = (ctypes.c_double * capacity)()
+    cu = (ctypes.c_double * capacity)()
+    n = ctypes.c_int64(0)
+    st = _lib.orthrus_attn_timing_samples(ctx, su, cu, capacity, ctypes.byref(n))
+    if st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_attn_timing_samples")
+    k = min(int(n.value), capacity)
+    return [(su[i], cu[i]) for i in range(k)]
 
 
 def orthrus_last_device_error(ctx, stream=None) -> int:

@@ -24,6 +24,23 @@ struct orthrus_ctx {
     std::vector<Pending> pending;
     double sum_us[2] = {0.0, 0.0};
     int64_t launches[2] = {0, 0};
+    // takes a pair of events from the free list (or creates them); false on a HIP error, nothing taken
+    bool take_events(hipEvent_t *start, hipEvent_t *stop)
+    {
+        hipEvent_t got[2] = {nullptr, nullptr};
+        for (int k = 0; k < 2; ++k) {
+            if (!free_events.empty()) {
+                got[k] = free_events.back();
+                free_events.pop_back();
+            } else if (hipEventCreate(&got[k]) != hipSuccess) {
+                if (k == 1) free_events.push_back(got[0]);
+                return false;
+            }
+        }
+        *start = got[0];
+        *stop = got[1];
+        return true;
+    }
 };
 
 namespace {
@@ -90,9 +107,113 @@ int consensus_chunks(const orthrus_params *p)
     return (p->vocab + ce - 1) / ce;
 }
 
-constexpr int kDefaultCUs = 256;  // MI355X; only used when sizing without a context
+constexpr int kDefaultCUs = 256;  // MI355X; used when sizing without a context
+
+// CU count the launch plan of a context's device is made for
+int plan_cus(const orthrus_ctx *ctx) { return ctx && ctx->num_cus > 0 ? ctx->num_cus : kDefaultCUs; }
+
+int64_t attn_workspace_for(const orthrus_params *p, int num_cus)
+{
+    orthrus_status s = check_params(p, true, false, true);
+    if (s != ORTHRUS_OK) return (int64_t)s;
+    orthrus::AttnPlan plan;
+    s = make_plan(p, num_cus, &plan);
+    if (s != ORTHRUS_OK) return (int64_t)s;
+    return (int64_t)(align_up(plan.part_o_bytes, 256) + align_up(plan.part_ml_bytes, 256));
+}
+
+int32_t attn_splits_for(const orthrus_params *p, int num_cus)
+{
+    orthrus_status s = check_params(p, true, false, true);
+    if (s != ORTHRUS_OK) return (int32_t)s;
+    orthrus::AttnPlan plan;
+    s = make_plan(p, num_cus, &plan);
+    if (s != ORTHRUS_OK) return (int32_t)s;
+    return plan.bal_wgs > 0 ? 0 : plan.num_splits;
+}
 
 }  // namespace
+
+// Kernel arguments of a decode-mode attention launch for `plan`.
+orthrus::AttnArgs decode_attn_args(const orthrus_ctx *ctx, const orthrus_params *p, const orthrus::AttnPlan &plan,
+                                   int view, const void *q, const void *k_blk, const void *v_blk,
+                                   const void *k_pool, const void *v_pool, const int32_t *page_table,
+                                   const int32_t *seq_lens, void *out, float *lse, void *workspace)
+{
+    orthrus::AttnArgs a;
+    a.q = (const uint16_t *)q; a.k_blk = (const uint16_t *)k_blk; a.v_blk = (const uint16_t *)v_blk;
+    a.k_pool = (const uint16_t *)k_pool; a.v_pool = (const uint16_t *)v_pool;
+    a.page_table = page_table; a.seq_lens = seq_lens;
+    a.out = (uint16_t *)out; a.lse = lse;
+    a.part_o = (float *)workspace;
+    a.part_ml = workspace ? (float *)((char *)workspace + align_up(plan.part_o_bytes, 256)) : nullptr;
+    a.err_word = ctx->err_word;
+    a.old_lens = nullptr; a.new_lens = nullptr; a.max_new = 0;
+    a.stride_page = p->pool_stride_page; a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok;
+    a.num_pages = p->num_pages;
+    a.batch = p->batch; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
+    a.group = p->num_q_heads / p->num_kv_heads; a.block_k = p->block_k; a.rows = plan.rows;
+    a.page_shift = log2_exact(p->page_size); a.max_pages_per_seq = p->max_pages_per_seq;
+    a.max_seq_len = p->max_seq_len; a.chunk_tokens = plan.chunk_tokens; a.num_splits = plan.num_splits;
+    a.bal_wgs = plan.bal_wgs;
+    a.kv_nt = plan.kv_nt;
+    a.view = view;
+    a.scale_log2e = p->sm_scale * 1.4426950408889634f;
+    return a;
+}
+
+static orthrus_status consensus_commit_impl(orthrus_ctx *ctx, const orthrus_params *p,
+                                        const float *ar_logits, const int32_t *draft_tokens,
+                                        const void *k_blk_ar, const void *v_blk_ar,
+                                        void *k_pool, void *v_pool,
+                                        const int32_t *page_table, int32_t *seq_lens,
+                                        int32_t *accept_len, int32_t *num_committed,
+                                        int32_t *out_tokens, int32_t *next_anchor,
+                                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx) return ORTHRUS_EINVAL;
+    if ((k_blk_ar == nullptr) != (v_blk_ar == nullptr)) return ORTHRUS_EINVAL;
+    const bool do_commit = k_blk_ar != nullptr;
+    orthrus_status s = check_params(p, false, true, do_commit);
+    if (s != ORTHRUS_OK) return s;
+    if (!ar_logits || !draft_tokens || !accept_len || !num_committed || !out_tokens || !next_anchor)
+        return ORTHRUS_EINVAL;
+    if (((uintptr_t)ar_logits) & 3) return ORTHRUS_EINVAL;
+    if (do_commit) {
+        if (!k_pool || !v_pool || !page_table || !seq_lens || p->num_layers <= 0) return ORTHRUS_EINVAL;
+        if (p->num_layers > 65535) return ORTHRUS_EUNSUPPORTED;
+        const uintptr_t al = (uintptr_t)k_blk_ar | (uintptr_t)v_blk_ar | (uintptr_t)k_pool | (uintptr_t)v_pool;
+        if (al & 15) return ORTHRUS_EINVAL;
+    }
+    if (p->batch == 0) return ORTHRUS_OK;
+    const size_t rows = (size_t)p->batch * p->block_k;
+    const size_t chunks = (size_t)consensus_chunks(p);
+    if (rows * chunks > 0x7fffffffull) return ORTHRUS_EUNSUPPORTED;
+    const size_t o1 = align_up(rows * chunks * sizeof(float), 256);
+    const size_t o2 = o1 + align_up(rows * chunks * sizeof(int32_t), 256);
+    const size_t need = o2 + align_up((size_t)p->batch * 2 * sizeof(int32_t), 256);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return ORTHRUS_EWORKSPACE;
+
+    orthrus::ConsensusArgs a;
+    a.ar_logits = ar_logits; a.draft_tokens = draft_tokens;
+    a.k_blk_ar = (const uint16_t *)k_blk_ar; a.v_blk_ar = (const uint16_t *)v_blk_ar;
+    a.k_pool = (uint16_t *)k_pool; a.v_pool = (uint16_t *)v_pool;
+    a.page_table = page_table; a.seq_lens = seq_lens;
+    a.accept_len = accept_len; a.num_committed = num_committed; a.out_tokens = out_tokens; a.next_anchor = next_anchor;
+    a.part_val = (float *)workspace;
+    a.part_idx = (int32_t *)((char *)workspace + o1);
+    a.commit_info = (int32_t *)((char *)workspace + o2);
+    a.err_word = ctx->err_word;
+    a.stride_layer = p->pool_stride_layer; a.stride_page = p->pool_stride_page;
+    a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok; a.num_pages = p->num_pages;
+    a.batch = p->batch; a.block_k = p->block_k; a.vocab = p->vocab; a.num_layers = p->num_layers;
+    a.num_kv_heads = p->num_kv_heads; a.head_dim = p->head_dim;
+    a.page_shift = do_commit ? log2_exact(p->page_size) : 0; a.max_pages_per_seq = p->max_pages_per_seq;
+    a.chunks = (int)chunks; a.chunk_elems = orthrus::consensus_chunk_elems(); a.do_commit = do_commit ? 1 : 0;
+    hipError_t e = orthrus::launch_consensus(a, (hipStream_t)stream);
+    return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
 
 extern "C" {
 
@@ -140,24 +261,15 @@ orthrus_status orthrus_destroy(orthrus_ctx *ctx)
     return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
 }
 
-int32_t orthrus_attn_num_splits(const orthrus_params *p)
+int32_t orthrus_attn_num_splits(const orthrus_params *p) { return attn_splits_for(p, kDefaultCUs); }
+int64_t orthrus_attn_workspace_bytes(const orthrus_params *p) { return attn_workspace_for(p, kDefaultCUs); }
+int32_t orthrus_attn_num_splits_on(const orthrus_ctx *ctx, const orthrus_params *p)
 {
-    orthrus_status s = check_params(p, true, false, true);
-    if (s != ORTHRUS_OK) return (int32_t)s;
-    orthrus::AttnPlan plan;
-    s = make_plan(p, kDefaultCUs, &plan);
-    if (s != ORTHRUS_OK) return (int32_t)s;
-    return plan.bal_wgs > 0 ? 0 : plan.num_splits;
+    return ctx ? attn_splits_for(p, plan_cus(ctx)) : (int32_t)ORTHRUS_EINVAL;
 }
-
-int64_t orthrus_attn_workspace_bytes(const orthrus_params *p)
+int64_t orthrus_attn_workspace_bytes_on(const orthrus_ctx *ctx, const orthrus_params *p)
 {
-    orthrus_status s = check_params(p, true, false, true);
-    if (s != ORTHRUS_OK) return (int64_t)s;
-    orthrus::AttnPlan plan;
-    s = make_plan(p, kDefaultCUs, &plan);
-    if (s != ORTHRUS_OK) return (int64_t)s;
-    return (int64_t)(align_up(plan.part_o_bytes, 256) + align_up(plan.part_ml_bytes, 256));
+    return ctx ? attn_workspace_for(p, plan_cus(ctx)) : (int64_t)ORTHRUS_EINVAL;
 }
 
 int64_t orthrus_consensus_workspace_bytes(const orthrus_params *p)
@@ -187,51 +299,22 @@ orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p,
     if (al & 15) return ORTHRUS_EINVAL;
     if (p->batch == 0) return ORTHRUS_OK;
     orthrus::AttnPlan plan;
-    // sized with the same CU count as the workspace query, so both always agree
-    s = make_plan(p, kDefaultCUs, &plan);
+    // planned for the device the context was created on (orthrus_attn_workspace_bytes_on gives the size
+    // for exactly this plan; the context-free query assumes the full 256-CU part)
+    s = make_plan(p, plan_cus(ctx), &plan);
     if (s != ORTHRUS_OK) return s;
     const size_t need = align_up(plan.part_o_bytes, 256) + align_up(plan.part_ml_bytes, 256);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return ORTHRUS_EWORKSPACE;
 
-    orthrus::AttnArgs a;
-    a.q = (const uint16_t *)q; a.k_blk = (const uint16_t *)k_blk; a.v_blk = (const uint16_t *)v_blk;
-    a.k_pool = (const uint16_t *)k_pool; a.v_pool = (const uint16_t *)v_pool;
-    a.page_table = page_table; a.seq_lens = seq_lens;
-    a.out = (uint16_t *)out; a.lse = lse;
-    a.part_o = (float *)workspace;
-    a.part_ml = (float *)((char *)workspace + align_up(plan.part_o_bytes, 256));
-    a.err_word = ctx->err_word;
-    a.old_lens = nullptr; a.new_lens = nullptr; a.max_new = 0;
-    a.stride_page = p->pool_stride_page; a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok;
-    a.num_pages = p->num_pages;
-    a.batch = p->batch; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
-    a.group = p->num_q_heads / p->num_kv_heads; a.block_k = p->block_k; a.rows = plan.rows;
-    a.page_shift = log2_exact(p->page_size); a.max_pages_per_seq = p->max_pages_per_seq;
-    a.max_seq_len = p->max_seq_len; a.chunk_tokens = plan.chunk_tokens; a.num_splits = plan.num_splits;
-    a.bal_wgs = plan.bal_wgs;
-    a.kv_nt = plan.kv_nt;
-    a.view = (int)view;
-    a.scale_log2e = p->sm_scale * 1.4426950408889634f;
+    orthrus::AttnArgs a = decode_attn_args(ctx, p, plan, view, q, k_blk, v_blk, k_pool, v_pool, page_table, seq_lens, out,
+                                           lse, workspace);
     orthrus::AttnLaunchEvents ev;
     if (ctx->timing) {
         ev.on = true;
-        bool ok = true;
-        for (int k = 0; k < 2 && ok; ++k) {
-            for (hipEvent_t *slot : {&ev.start[k], &ev.stop[k]}) {
-                if (!ctx->free_events.empty()) {
-                    *slot = ctx->free_events.back();
-                    ctx->free_events.pop_back();
-                } else if (hipEventCreate(slot) != hipSuccess) {
-                    *slot = nullptr;
-                    ok = false;
-                    break;
-                }
-            }
-        }
-        if (!ok) {  // hand back what was taken; nothing has been launched
-            for (int k = 0; k < 2; ++k)
-                for (hipEvent_t e2 : {ev.start[k], ev.stop[k]})
-                    if (e2) ctx->free_events.push_back(e2);
+        if (!ctx->take_events(&ev.start[0], &ev.stop[0])) return ORTHRUS_EHIP;
+        if (!ctx->take_events(&ev.start[1], &ev.stop[1])) {  // hand back what was taken; nothing has been launched
+            ctx->free_events.push_back(ev.start[0]);
+            ctx->free_events.push_back(ev.stop[0]);
             return ORTHRUS_EHIP;
         }
     }
@@ -392,6 +475,64 @@ orthrus_status orthrus_attn_timing_read(orthrus_ctx *ctx, double *split_us, int6
     return st;
 }
 
+orthrus_status orthrus_attn_timing_samples(orthrus_ctx *ctx, double *split_us, double *combine_us, int64_t capacity,
+                                          int64_t *count)
+{
+    if (!ctx || !split_us || !combine_us || !count || capacity < 0) return ORTHRUS_EINVAL;
+    orthrus_status st = ORTHRUS_OK;
+    int64_t n = 0;
+    // pending holds the timed kernels in launch order: a split-kernel record opens a call's sample, the
+    // combine record that follows it (if the call had one) completes it
+    for (auto &pd : ctx->pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(pd.stop) != hipSuccess || hipEventElapsedTime(&ms, pd.start, pd.stop) != hipSuccess)
+            st = ORTHRUS_EHIP;
+        if (pd.kind == 0) {
+            if (n < capacity) { split_us[n] = (double)ms * 1000.0; combine_us[n] = 0.0; }
+            ++n;
+        } else if (n > 0 && n <= capacity) {
+            combine_us[n - 1] = (double)ms * 1000.0;
+        }
+        ctx->free_events.push_back(pd.start);
+        ctx->free_events.push_back(pd.stop);
+    }
+    ctx->pending.clear();
+    ctx->sum_us[0] = ctx->sum_us[1] = 0.0;
+    ctx->launches[0] = ctx->launches[1] = 0;
+    *count = n;
+    return st;
+}
+
+orthrus_status orthrus_kv_stream_probe(orthrus_ctx *ctx, const orthrus_params *p, const void *k_pool,
+                                       const void *v_pool, const int32_t *page_table, const int32_t *seq_lens,
+                                       void *stream)
+{
+    if (!ctx) return ORTHRUS_EINVAL;
+    orthrus_status s = check_params(p, true, false, true);
+    if (s != ORTHRUS_OK) return s;
+    if (!k_pool || !v_pool || !page_table || !seq_lens) return ORTHRUS_EINVAL;
+    if (((uintptr_t)k_pool | (uintptr_t)v_pool) & 15) return ORTHRUS_EINVAL;
+    if (p->batch == 0) return ORTHRUS_OK;
+    orthrus::AttnPlan plan;
+    s = make_plan(p, plan_cus(ctx), &plan);  // the partition the attention call would use
+    if (s != ORTHRUS_OK) return s;
+    const orthrus::AttnArgs a = decode_attn_args(ctx, p, plan, (int)ORTHRUS_VIEW_DIFFUSION, nullptr, nullptr, nullptr,
+                                                 k_pool, v_pool, page_table, seq_lens, nullptr, nullptr, nullptr);
+    hipEvent_t start = nullptr, stop = nullptr;
+    if (ctx->timing && !ctx->take_events(&start, &stop)) return ORTHRUS_EHIP;
+    hipError_t e = orthrus::launch_kv_stream_probe(a, plan, p->head_dim, (hipStream_t)stream, start, stop);
+    if (start) {
+        if (e == hipSuccess) ctx->pending.push_back({start, stop, 0});
+        else { ctx->free_events.push_back(start); ctx->free_events.push_back(stop); }
+    }
+    return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+}
+
+#ifndef ORTHRUS_BUILD_ID
+#define ORTHRUS_BUILD_ID "unknown"
+#endif
+const char *orthrus_build_id(void) { return ORTHRUS_BUILD_ID; }
+
 orthrus_status orthrus_consensus_commit(orthrus_ctx *ctx, const orthrus_params *p,
                                         const float *ar_logits, const int32_t *draft_tokens,
                                         const void *k_blk_ar, const void *v_blk_ar,
@@ -401,47 +542,9 @@ orthrus_status orthrus_consensus_commit(orthrus_ctx *ctx, const orthrus_params *
                                         int32_t *out_tokens, int32_t *next_anchor,
                                         void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!ctx) return ORTHRUS_EINVAL;
-    if ((k_blk_ar == nullptr) != (v_blk_ar == nullptr)) return ORTHRUS_EINVAL;
-    const bool do_commit = k_blk_ar != nullptr;
-    orthrus_status s = check_params(p, false, true, do_commit);
-    if (s != ORTHRUS_OK) return s;
-    if (!ar_logits || !draft_tokens || !accept_len || !num_committed || !out_tokens || !next_anchor)
-        return ORTHRUS_EINVAL;
-    if (((uintptr_t)ar_logits) & 3) return ORTHRUS_EINVAL;
-    if (do_commit) {
-        if (!k_pool || !v_pool || !page_table || !seq_lens || p->num_layers <= 0) return ORTHRUS_EINVAL;
-        if (p->num_layers > 65535) return ORTHRUS_EUNSUPPORTED;
-        const uintptr_t al = (uintptr_t)k_blk_ar | (uintptr_t)v_blk_ar | (uintptr_t)k_pool | (uintptr_t)v_pool;
-        if (al & 15) return ORTHRUS_EINVAL;
-    }
-    if (p->batch == 0) return ORTHRUS_OK;
-    const size_t rows = (size_t)p->batch * p->block_k;
-    const size_t chunks = (size_t)consensus_chunks(p);
-    if (rows * chunks > 0x7fffffffull) return ORTHRUS_EUNSUPPORTED;
-    const size_t o1 = align_up(rows * chunks * sizeof(float), 256);
-    const size_t o2 = o1 + align_up(rows * chunks * sizeof(int32_t), 256);
-    const size_t need = o2 + align_up((size_t)p->batch * 2 * sizeof(int32_t), 256);
-    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return ORTHRUS_EWORKSPACE;
-
-    orthrus::ConsensusArgs a;
-    a.ar_logits = ar_logits; a.draft_tokens = draft_tokens;
-    a.k_blk_ar = (const uint16_t *)k_blk_ar; a.v_blk_ar = (const uint16_t *)v_blk_ar;
-    a.k_pool = (uint16_t *)k_pool; a.v_pool = (uint16_t *)v_pool;
-    a.page_table = page_table; a.seq_lens = seq_lens;
-    a.accept_len = accept_len; a.num_committed = num_committed; a.out_tokens = out_tokens; a.next_anchor = next_anchor;
-    a.part_val = (float *)workspace;
-    a.part_idx = (int32_t *)((char *)workspace + o1);
-    a.commit_info = (int32_t *)((char *)workspace + o2);
-    a.err_word = ctx->err_word;
-    a.stride_layer = p->pool_stride_layer; a.stride_page = p->pool_stride_page;
-    a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok; a.num_pages = p->num_pages;
-    a.batch = p->batch; a.block_k = p->block_k; a.vocab = p->vocab; a.num_layers = p->num_layers;
-    a.num_kv_heads = p->num_kv_heads; a.head_dim = p->head_dim;
-    a.page_shift = do_commit ? log2_exact(p->page_size) : 0; a.max_pages_per_seq = p->max_pages_per_seq;
-    a.chunks = (int)chunks; a.chunk_elems = orthrus::consensus_chunk_elems(); a.do_commit = do_commit ? 1 : 0;
-    hipError_t e = orthrus::launch_consensus(a, (hipStream_t)stream);
-    return e == hipSuccess ? ORTHRUS_OK : ORTHRUS_EHIP;
+    return consensus_commit_impl(ctx, p, ar_logits, draft_tokens, k_blk_ar, v_blk_ar, k_pool, v_pool, page_table,
+                                 seq_lens, accept_len, num_committed, out_tokens, next_anchor, workspace,
+                                 workspace_bytes, stream);
 }
 
 int64_t orthrus_sampling_workspace_bytes(const orthrus_params *p)

@@ -4,7 +4,8 @@
 //
 // Work decomposition
 //   grid   = one workgroup per (split, KV head g, sequence b).  A workgroup streams cache tokens
-//            [split*chunk, min(L_b, (split+1)*chunk)) of KV head g once and serves all R = G*K
+//            [split*chunk_b, min(L_b, (split+1)*chunk_b)) of KV head g once (chunk_b: the sequence's own
+//            length cut into equal runs of whole tiles) and serves all R = G*K
 //            query rows that share that KV head (G query heads x K block rows).
 //            Workgroups are numbered with the sequence index fastest and the KV head slowest
 //            (consecutive ids go to different XCDs; see the kernel).
@@ -36,6 +37,8 @@
 #include <hip/hip_ext.h>
 
 #include <type_traits>
+
+#pragma clang diagnostic ignored "-Winline-asm"  // the direct-to-LDS loads below name M0 as clobbered
 
 namespace orthrus {
 
@@ -107,6 +110,15 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Cache tokens per split of a sequence of L tokens cut into `splits` runs of whole 32-token tiles
+// (at least one tile, so that the arithmetic also holds for an empty sequence).
+__host__ __device__ __forceinline__ int split_chunk(int L, int splits)
+{
+    const int tiles = (L + 31) >> 5;
+    const int per = (tiles + splits - 1) / splits;
+    return (per > 0 ? per : 1) * 32;
+}
+
 template <int D>
 struct AttnGeom {
     static constexpr int CH = D / 8;          // 16-byte chunks per K/V row
@@ -143,10 +155,15 @@ struct AttnGeom {
 // attn_combine_kernel finds again from the same arithmetic.  With ragged lengths every workgroup
 // still gets the same number of tiles, and with N = resident workgroups nothing queues behind
 // the dispatcher.  Each segment runs the pipeline from empty (fill, loop, drain).
-template <int D, int W, int NS, int PREFILL = 0, int BALANCED = 0>
+//
+// PROBE = 1 is the measurement form behind orthrus_kv_stream_probe: the loader wave streams exactly the
+// tiles of the call, the compute waves only keep the barriers (no queries, no arithmetic, nothing is
+// written), so the launch takes as long as this kernel's K/V stream alone.
+template <int D, int W, int NS, int PREFILL = 0, int BALANCED = 0, int PROBE = 0>
 __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnArgs a)
 {
     static_assert(!(PREFILL && BALANCED), "the balanced partition is a decode mode");
+    static_assert(!PROBE || (W == 1 && !PREFILL), "the stream probe is a decode-mode kernel with one idle compute wave");
     using Gm = AttnGeom<D>;
     constexpr int CH = Gm::CH, ROWB = Gm::ROWB, RPI = Gm::RPI, NI = Gm::NI, GS = Gm::GS;
     constexpr int TILE_B = Gm::TILE_B, STAGE_B = Gm::STAGE_B, KSTEPS = Gm::KSTEPS, DBLK = Gm::DBLK;
@@ -287,9 +304,13 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
                 final_out = true;
             } else {
                 const int L = seq_len(b);
-                t_begin = split * a.chunk_tokens;
+                // The sequence's own length, not the host's bound on it, is cut into num_splits runs of
+                // whole tiles: the pieces of a sequence stay equal however loose the bound is (it only
+                // sized the grid), e.g. when a decode loop bumps it by K per step without reading back.
+                const int chunk = split_chunk(L, a.num_splits);
+                t_begin = split * chunk;
                 if (split > 0 && t_begin >= L) return false;  // nothing of this sequence falls in the split
-                t_end = min(L, t_begin + a.chunk_tokens);
+                t_end = min(L, t_begin + chunk);
                 n_cache = t_end > t_begin ? (t_end - t_begin + 31) >> 5 : 0;
                 n_tiles = n_cache + (split == 0 ? 1 : 0);  // split 0 ends with the in-block tile
                 final_out = a.num_splits == 1;
@@ -308,9 +329,10 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
     // Direct global->LDS load of 64 x 16 bytes: lane's bytes land at lds_addr + lane*16.  Issued
     // through inline assembly so that whole tiles can stay in flight while older ones are computed;
     // completion is awaited explicitly with s_waitcnt vmcnt (loads return in order).  M0 carries the
-    // LDS destination; nothing else in this kernel reads M0, and the compiler rewrites M0 itself
-    // right before any instruction of its own that needs it.  Two address forms: a 64-bit address per
-    // lane, or a wave-uniform 64-bit base plus a 32-bit byte offset per lane.
+    // LDS destination and is declared clobbered, so the compiler never carries a value of its own in M0
+    // across one of these statements (M0 is a reserved register, which clang remarks on for any clobber
+    // list that names it; the remark is switched off for this file).  Two address forms: a 64-bit
+    // address per lane, or a wave-uniform 64-bit base plus a 32-bit byte offset per lane.
     //
     // a.kv_nt selects the non-temporal form of the loads: when one call streams more K/V than the
     // last-level cache holds, nothing of it is there for the next call anyway, and loads that do not
@@ -322,24 +344,24 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
             asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
                          :
                          : "v"(gp), "s"(lds_addr)
-                         : "memory");
+                         : "memory", "m0");
         else
             asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                          :
                          : "v"(gp), "s"(lds_addr)
-                         : "memory");
+                         : "memory", "m0");
     };
     auto dma16s = [&](auto nt, const uint16_t *base, uint32_t voff, uint32_t lds_addr) __attribute__((always_inline)) {
         if constexpr (decltype(nt)::value)
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
                          :
                          : "v"(voff), "s"(base), "s"(lds_addr)
-                         : "memory");
+                         : "memory", "m0");
         else
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                          :
                          : "v"(voff), "s"(base), "s"(lds_addr)
-                         : "memory");
+                         : "memory", "m0");
     };
 
     // Page ids of the two 16-token halves of cache tile t (the second repeats the first when that
@@ -396,7 +418,7 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
                     dma16(nt, pool + off, dst + (id < NI ? 0 : TILE_B) + u * GS);
                 }
             }
-        } else {
+        } else if constexpr (!PROBE) {  // (the stream probe has no block inputs: its in-block tile stays empty)
 #pragma unroll
             for (int e = 0; e < LPT; ++e) {
                 const int id = e;
@@ -448,6 +470,14 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
     }
 
     // ---- compute waves
+    if constexpr (PROBE) {
+        for (;;) {
+            for (int i = 0; i < n_tiles; ++i) wg_barrier();
+            if (!BALANCED || !open_item()) break;
+            wg_barrier();
+        }
+        return;
+    }
     // lane-invariant LDS read offsets inside one stage
     int kb[KSTEPS / 2];  // K operand: row `col`, chunks 4q'..4q'+3 where q' = q ^ (xm >> 2)
     {
@@ -690,7 +720,8 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
     } else {
         int L = ((const const_i32 *)a.seq_lens)[b];
         L = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
-        live = (L + a.chunk_tokens - 1) / a.chunk_tokens;
+        const int chunk = split_chunk(L, a.num_splits);  // the split kernel's cut of this sequence
+        live = (L + chunk - 1) / chunk;
         live = live < 1 ? 1 : (live > a.num_splits ? a.num_splits : live);
         first_slot = rest_slot = (size_t)unit * a.num_splits;
         slot_step = 1;
@@ -871,6 +902,30 @@ static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStr
         e = hipGetLastError();
     }
     return e;
+}
+
+// The stream probe: the same grid, partition and loader as the attention call planned by `plan`, with one
+// idle compute wave per workgroup.
+template <int D>
+static hipError_t launch_probe_d(const AttnArgs &a, const AttnPlan &plan, hipStream_t stream, hipEvent_t start,
+                                 hipEvent_t stop)
+{
+    const bool bal = plan.bal_wgs > 0;
+    auto kern = bal ? attn_split_kernel<D, 1, kStages, 0, 1, 1> : attn_split_kernel<D, 1, kStages, 0, 0, 1>;
+    dim3 grid(bal ? (unsigned)plan.bal_wgs : (unsigned)plan.num_splits * (unsigned)a.num_kv_heads * (unsigned)a.batch);
+    const size_t lds = lds_need(D);
+    if (start && stop) hipExtLaunchKernelGGL(kern, grid, dim3(128), lds, stream, start, stop, 0, a);
+    else hipLaunchKernelGGL(kern, grid, dim3(128), lds, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_stream_probe(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream,
+                                  hipEvent_t start, hipEvent_t stop)
+{
+    if (a.batch == 0) return hipSuccess;
+    if (head_dim == 128) return launch_probe_d<128>(a, plan, stream, start, stop);
+    if (head_dim == 64) return launch_probe_d<64>(a, plan, stream, start, stop);
+    return hipErrorInvalidValue;
 }
 
 template <int D, int W>

@@ -5,7 +5,8 @@
 //   argmax_partial_kernel  grid (row * chunks + chunk): each workgroup scans one chunk of one logits
 //                          row with 16-byte loads and reduces (value, index) through wavefront
 //                          shuffles; one (value, index) pair per chunk goes to the workspace.
-//   accept_commit_kernel   grid (sequence): the first wave finishes the K row argmaxes, finds the
+//   accept_commit_kernel   grid (sequence): the four waves finish the K row argmaxes (chunk pairs spread
+//                          over the lanes, wavefront-shuffle reduction), the first wave finds the
 //                          accepted prefix with a wavefront ballot, writes tokens/lengths and checks
 //                          that the appended positions are mapped; then the whole workgroup copies
 //                          the appended K/V rows into their pages (up to kInlineLayers layers).
@@ -52,27 +53,6 @@ __device__ __forceinline__ void wave_best(float &bv, int &bi)
 }
 
 constexpr int kInlineLayers = 2;
-
-// Copy rows 0..m-1 of the AR view's block K/V of (sequence b, layer) to token positions L..L+m-1.
-__device__ __forceinline__ void append_rows(const ConsensusArgs &a, int b, int layer, int L, int m, int tid, int nthreads)
-{
-    const int K = a.block_k, H = a.num_kv_heads, d = a.head_dim;
-    const int cpr = d / 8;  // 16-byte chunks per row
-    const int per_tok = H * cpr;
-    const int total = m * per_tok;
-    const int P = 1 << a.page_shift;
-    for (int e = tid; e < total; e += nthreads) {
-        const int k = e / per_tok, rem = e - k * per_tok;
-        const int g = rem / cpr, ch = rem - g * cpr;
-        const int pos = L + k;
-        const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + (pos >> a.page_shift)];
-        const int64_t src = ((((int64_t)layer * a.batch + b) * K + k) * H + g) * d + ch * 8;
-        const int64_t dst = (int64_t)layer * a.stride_layer + (int64_t)pg * a.stride_page +
-                            (int64_t)g * a.stride_head + (int64_t)(pos & (P - 1)) * a.stride_tok + ch * 8;
-        *(uint4 *)(a.k_pool + dst) = *(const uint4 *)(a.k_blk_ar + src);
-        *(uint4 *)(a.v_pool + dst) = *(const uint4 *)(a.v_blk_ar + src);
-    }
-}
 
 __global__ void __launch_bounds__(256) argmax_partial_kernel(const ConsensusArgs a)
 {
@@ -134,22 +114,47 @@ __global__ void __launch_bounds__(256) accept_commit_kernel(const ConsensusArgs 
     const int b = blockIdx.x, tid = threadIdx.x;
     const int K = a.block_k;
     __shared__ int s_L, s_m;
+    __shared__ int s_am[32];
+    // ---- row argmaxes: wave w finishes rows w, w+4, ...; a lane takes the chunk pairs lane, lane+64, ...
+    // All loads of a wave's rows go out before the first reduction, so the phase costs one memory round
+    // trip, not one per chunk.  A lane without a chunk holds (-inf, INT_MAX), which every real pair outranks.
+    {
+        const int wave = tid >> 6, lane = tid & 63;
+        constexpr int kRowsPerWave = 8;  // block_k <= 32 rows over 4 waves
+        float bv[kRowsPerWave];
+        int bi[kRowsPerWave];
+#pragma unroll
+        for (int u = 0; u < kRowsPerWave; ++u) {
+            const int k = wave + 4 * u;
+            bv[u] = -INFINITY;
+            bi[u] = 0x7fffffff;
+            if (k < K) {
+                const int64_t r = ((int64_t)b * K + k) * a.chunks;
+                for (int ch = lane; ch < a.chunks; ch += 64) {
+                    const float v = a.part_val[r + ch];
+                    const int i = a.part_idx[r + ch];
+                    if (outranks(v, i, bv[u], bi[u])) { bv[u] = v; bi[u] = i; }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kRowsPerWave; ++u) {
+            const int k = wave + 4 * u;
+            if (k < K) {  // wave-uniform
+                wave_best(bv[u], bi[u]);
+                if (lane == 0) s_am[k] = bi[u];
+            }
+        }
+    }
+    __syncthreads();
     // ---- accept: the first wave, lane k < K owns block row k of sequence b
     if (tid < 64) {
         const int lane = tid;
         int am = -1;
         bool match = false;
         if (lane < K) {
-            const int64_t r = (int64_t)b * K + lane;
-            float v0 = a.part_val[r * a.chunks];
-            int i0 = a.part_idx[r * a.chunks];
-            for (int ch = 1; ch < a.chunks; ++ch) {
-                const float v = a.part_val[r * a.chunks + ch];
-                const int i = a.part_idx[r * a.chunks + ch];
-                if (outranks(v, i, v0, i0)) { v0 = v; i0 = i; }
-            }
-            am = i0;
-            match = a.draft_tokens[r] == am;
+            am = s_am[lane];
+            match = a.draft_tokens[(int64_t)b * K + lane] == am;
         }
         // accepted prefix = run of matching rows starting at row 0
         const unsigned long long mism = ~__ballot(match);           // lanes >= K never match
@@ -159,27 +164,7 @@ __global__ void __launch_bounds__(256) accept_commit_kernel(const ConsensusArgs 
         const int anchor = __shfl(am, m - 1);
         int committed = m;
         int L = 0;
-        if (a.do_commit) {
-            L = a.seq_lens[b];
-            bool bad = false;
-            if (lane < m) {
-                const int pos = L + lane;
-                const int slot = pos >> a.page_shift;
-                if (L < 0 || slot >= a.max_pages_per_seq) bad = true;
-                else {
-                    const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + slot];
-                    bad = pg < 0 || pg >= a.num_pages;
-                }
-            }
-            const bool any_bad = __ballot(bad) != 0ull;
-            if (any_bad) committed = 0;
-            if (lane == 0) {
-                a.commit_info[b * 2] = L;
-                a.commit_info[b * 2 + 1] = committed;
-                if (any_bad) atomicExch(a.err_word, -4);
-                else a.seq_lens[b] = L + m;
-            }
-        }
+        if (a.do_commit) committed = check_and_bump(a, b, lane, m, &L);
         if (lane == 0) {
             a.accept_len[b] = n_acc;
             a.num_committed[b] = committed;

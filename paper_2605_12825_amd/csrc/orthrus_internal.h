@@ -12,7 +12,7 @@ struct AttnPlan {
     int rows;          // R = G * K query rows per KV head
     int waves;         // compute waves per workgroup = 32-row blocks (1 .. 8)
     int rows_padded;   // waves * 32
-    int chunk_tokens;  // cache tokens per split (multiple of 32)
+    int chunk_tokens;  // cache tokens per split at the host bound (the kernels cut each sequence by its own length)
     int num_splits;    // splits per (sequence, KV head)
     int bal_wgs;       // > 0: balanced partition over this many workgroups instead of fixed splits
     int kv_nt;         // 1: the call streams more K/V than the last-level cache holds: non-temporal tile loads
@@ -66,6 +66,60 @@ struct SamplingArgs {
     float inv_temperature;
 };
 
+// ---- commit helpers shared by the greedy and the sampling consensus kernels (device code)
+#if defined(__HIPCC__)
+// Copy rows 0..m-1 of the AR view's block K/V of (sequence b, layer) to token positions L..L+m-1 of the
+// pools (Fig. 2(b): only the accepted tokens' K/V enters the shared cache), as 16-byte chunks.
+__device__ __forceinline__ void append_rows(const ConsensusArgs &a, int b, int layer, int L, int m, int tid, int nthreads)
+{
+    const int K = a.block_k, H = a.num_kv_heads, d = a.head_dim;
+    const int cpr = d / 8;  // 16-byte chunks per row
+    const int per_tok = H * cpr;
+    const int total = m * per_tok;
+    const int P = 1 << a.page_shift;
+    for (int e = tid; e < total; e += nthreads) {
+        const int k = e / per_tok, rem = e - k * per_tok;
+        const int g = rem / cpr, ch = rem - g * cpr;
+        const int pos = L + k;
+        const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + (pos >> a.page_shift)];
+        const int64_t src = ((((int64_t)layer * a.batch + b) * K + k) * H + g) * d + ch * 8;
+        const int64_t dst = (int64_t)layer * a.stride_layer + (int64_t)pg * a.stride_page +
+                            (int64_t)g * a.stride_head + (int64_t)(pos & (P - 1)) * a.stride_tok + ch * 8;
+        *(uint4 *)(a.k_pool + dst) = *(const uint4 *)(a.k_blk_ar + src);
+        *(uint4 *)(a.v_pool + dst) = *(const uint4 *)(a.v_blk_ar + src);
+    }
+}
+
+// Run by the first wave of a sequence's workgroup once it knows m, the number of rows to append: checks
+// that positions L..L+m-1 (L = seq_lens[b]) are mapped, then either bumps the length or flags the
+// capacity error and leaves the sequence alone.  Records (L, rows to append) for the copy.  Returns the
+// rows that will be appended (m or 0); *L_out = L.  Every lane of the wave must call it.
+__device__ __forceinline__ int check_and_bump(const ConsensusArgs &a, int b, int lane, int m, int *L_out)
+{
+    const int L = a.seq_lens[b];
+    bool bad = false;
+    if (lane < m) {
+        const int pos = L + lane;
+        const int slot = pos >> a.page_shift;
+        if (L < 0 || slot >= a.max_pages_per_seq) bad = true;
+        else {
+            const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + slot];
+            bad = pg < 0 || pg >= a.num_pages;
+        }
+    }
+    const bool any_bad = __ballot(bad) != 0ull;
+    const int committed = any_bad ? 0 : m;
+    if (lane == 0) {
+        a.commit_info[b * 2] = L;
+        a.commit_info[b * 2 + 1] = committed;
+        if (any_bad) atomicExch(a.err_word, -4);
+        else a.seq_lens[b] = L + m;
+    }
+    *L_out = L;
+    return committed;
+}
+#endif
+
 // Optional start/stop events of the two attention kernels of one call (index 0 = split kernel,
 // 1 = combine kernel).  When `on`, the launcher attaches them to the dispatches themselves, so that
 // hipEventElapsedTime(start, stop) is the kernel's own execution time without any marker in between.
@@ -84,6 +138,10 @@ hipError_t launch_prefill_attn(const AttnArgs &a, int head_dim, hipStream_t stre
 hipError_t launch_consensus(const ConsensusArgs &a, hipStream_t stream);
 hipError_t launch_sampling_consensus(const SamplingArgs &a, hipStream_t stream);
 int consensus_chunk_elems();
+// Measurement helper: the attention call's own K/V stream with idle compute waves (same grid, same
+// partition, same loader, no arithmetic, nothing written).
+hipError_t launch_kv_stream_probe(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream,
+                                  hipEvent_t start, hipEvent_t stop);
 
 // Prefill front end (defined with the commit kernels): validates lengths and pages, records the lengths
 // before the call and the accepted new-token counts, bumps seq_lens, then copies the new K/V rows in.

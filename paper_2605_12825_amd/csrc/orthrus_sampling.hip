@@ -221,25 +221,6 @@ __global__ void __launch_bounds__(256) draw_partial_kernel(const SamplingArgs a)
     }
 }
 
-// Same row copy as the greedy path.
-__device__ __forceinline__ void append_rows_s(const ConsensusArgs &a, int b, int layer, int L, int m, int tid, int nthreads)
-{
-    const int K = a.block_k, H = a.num_kv_heads, d = a.head_dim;
-    const int cpr = d / 8, per_tok = H * cpr, total = m * per_tok;
-    const int P = 1 << a.page_shift;
-    for (int e = tid; e < total; e += nthreads) {
-        const int k = e / per_tok, rem = e - k * per_tok;
-        const int g = rem / cpr, ch = rem - g * cpr;
-        const int pos = L + k;
-        const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + (pos >> a.page_shift)];
-        const int64_t src = ((((int64_t)layer * a.batch + b) * K + k) * H + g) * d + ch * 8;
-        const int64_t dst = (int64_t)layer * a.stride_layer + (int64_t)pg * a.stride_page +
-                            (int64_t)g * a.stride_head + (int64_t)(pos & (P - 1)) * a.stride_tok + ch * 8;
-        *(uint4 *)(a.k_pool + dst) = *(const uint4 *)(a.k_blk_ar + src);
-        *(uint4 *)(a.v_pool + dst) = *(const uint4 *)(a.v_blk_ar + src);
-    }
-}
-
 __global__ void __launch_bounds__(256) sample_commit_kernel(const SamplingArgs a)
 {
     const ConsensusArgs &c = a.c;
@@ -277,26 +258,7 @@ __global__ void __launch_bounds__(256) sample_commit_kernel(const SamplingArgs a
         }
         const int last_tok = (j < K) ? repl : c.draft_tokens[(int64_t)b * K + K - 1];
         int committed = m, L = 0;
-        if (c.do_commit) {
-            L = c.seq_lens[b];
-            bool bad = false;
-            if (lane < m) {
-                const int pos = L + lane, slot = pos >> c.page_shift;
-                if (L < 0 || slot >= c.max_pages_per_seq) bad = true;
-                else {
-                    const int pg = c.page_table[(int64_t)b * c.max_pages_per_seq + slot];
-                    bad = pg < 0 || pg >= c.num_pages;
-                }
-            }
-            const bool any_bad = __ballot(bad) != 0ull;
-            if (any_bad) committed = 0;
-            if (lane == 0) {
-                c.commit_info[b * 2] = L;
-                c.commit_info[b * 2 + 1] = committed;
-                if (any_bad) atomicExch(c.err_word, -4);
-                else c.seq_lens[b] = L + m;
-            }
-        }
+        if (c.do_commit) committed = check_and_bump(c, b, lane, m, &L);
         if (lane == 0) {
             c.accept_len[b] = j;
             c.num_committed[b] = committed;
@@ -307,14 +269,14 @@ __global__ void __launch_bounds__(256) sample_commit_kernel(const SamplingArgs a
     }
     __syncthreads();
     if (c.do_commit && c.num_layers <= kSInlineLayers && s_m > 0)
-        for (int layer = 0; layer < c.num_layers; ++layer) append_rows_s(c, b, layer, s_L, s_m, tid, 256);
+        for (int layer = 0; layer < c.num_layers; ++layer) append_rows(c, b, layer, s_L, s_m, tid, 256);
 }
 
 __global__ void __launch_bounds__(256) sample_commit_layers_kernel(const SamplingArgs a)
 {
     const int b = blockIdx.x, layer = blockIdx.y;
     const int L = a.c.commit_info[b * 2], m = a.c.commit_info[b * 2 + 1];
-    if (m > 0) append_rows_s(a.c, b, layer, L, m, threadIdx.x, 256);
+    if (m > 0) append_rows(a.c, b, layer, L, m, threadIdx.x, 256);
 }
 
 hipError_t launch_sampling_consensus(const SamplingArgs &a, hipStream_t stream)

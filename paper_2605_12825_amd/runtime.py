@@ -44,13 +44,14 @@ class DecodeStep:
                                     num_pages=num_pages, num_splits=num_splits, num_layers=num_layers,
                                     vocab=vocab, sm_scale=sm_scale, **kw)
         self.ctx = B.orthrus_create(device)
-        self.num_splits = B.orthrus_attn_num_splits(self.params)
+        # plans and sizes for the device the context lives on
+        self.num_splits = B.orthrus_attn_num_splits_on(self.ctx, self.params)
         # workspace for every host bound on the lengths the caller may set later (see set_max_seq_len)
-        n = B.orthrus_attn_workspace_bytes(self.params)
+        n = B.orthrus_attn_workspace_bytes_on(self.ctx, self.params)
         lo = max_seq_len if min_seq_len_bound is None else min_seq_len_bound
         for bound in range(lo, max_seq_len, max(block_k, 1)):
             self.params.max_seq_len = bound
-            n = max(n, B.orthrus_attn_workspace_bytes(self.params))
+            n = max(n, B.orthrus_attn_workspace_bytes_on(self.ctx, self.params))
         self.params.max_seq_len = max_seq_len
         self.attn_ws = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
         self.cons_ws = None
@@ -65,7 +66,7 @@ class DecodeStep:
         and must not be below any current sequence length.
         """
         self.params.max_seq_len = int(bound)
-        self.num_splits = B.orthrus_attn_num_splits(self.params)
+        self.num_splits = B.orthrus_attn_num_splits_on(self.ctx, self.params)
 
     def close(self):
         if self.ctx:
@@ -114,6 +115,14 @@ class DecodeStep:
         """(split us, launches, combine us, launches) summed over the timed launches since the last read."""
         return B.orthrus_attn_timing_read(self.ctx)
 
+    def attn_timing_samples(self, capacity: int = 4096):
+        """[(split kernel us, combine kernel us)] per timed call since the last read, in launch order."""
+        return B.orthrus_attn_timing_samples(self.ctx, capacity)
+
+    def kv_stream_probe(self, k_pool, v_pool, page_table, seq_lens, stream=None) -> None:
+        """The attention call's K/V stream over this cache with idle compute waves (measurement)."""
+        B.orthrus_kv_stream_probe(self.ctx, self.params, k_pool, v_pool, page_table, seq_lens, stream)
+
     def device_error(self, stream=None) -> int:
         return B.orthrus_last_device_error(self.ctx, stream)
 
@@ -137,7 +146,7 @@ class DecodeStack:
         L, pages, H, P, d = k_pool.shape
         self.num_layers, self.temperature = num_layers, float(temperature)
         # forward passes of the diffusion view per cycle: 1 is the paper's single-step projection, 2 the
-        # multi-step denoising variant of its ablation (Section 4.4, Table 5); the passes run back to back
+        # multi-step denoising variant of its ablation (Section 5, Table 3); the passes run back to back
         # over the same buffers (whatever refines the block between them writes q_diff / k_blk_diff / v_blk_diff)
         self.diffusion_passes = int(diffusion_passes)
         if self.diffusion_passes < 1:

@@ -143,7 +143,7 @@ def test_stack_sampling_cycle_graph_replay_matches_eager():
 
 
 def test_two_diffusion_passes_per_cycle_leave_the_results_unchanged():
-    """The multi-step variant of the paper's ablation (Section 4.4) runs the diffusion view twice per cycle;
+    """The multi-step variant of the paper's ablation (Section 5, Table 3) runs the diffusion view twice per cycle;
     over unchanged inputs the second pass reproduces the first, eagerly and in a replayed graph."""
     w = _workload()
     kp, vp, pt, lens = _initial_state(w)
