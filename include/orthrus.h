@@ -203,6 +203,28 @@ orthrus_status orthrus_consensus_commit(orthrus_ctx *ctx, const orthrus_params *
                                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * orthrus_consensus_commit for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results, errors and
+ * kernels as orthrus_consensus_commit, minus the workspace: the chunk argmax pairs and the per-sequence
+ * commit record go to a fixed array of orthrus_noalloc_scratch_bytes() bytes (1 MiB) that is part of the
+ * library's device image, one copy per GPU, held until the process ends.  The call allocates nothing and
+ * frees nothing.  A problem that needs more than the array holds (orthrus_consensus_workspace_bytes(p) >
+ * orthrus_noalloc_scratch_bytes(): roughly batch * block_k * ceil(vocab / 8192) > 130000) returns
+ * ORTHRUS_EWORKSPACE and launches nothing.  Every call on one GPU shares that GPU's array: calls that
+ * overlap in time on one GPU (two streams, two contexts, two threads) race on it; calls queued on one
+ * stream do not.  Nothing in the array has to be cleared between calls: each call writes every entry
+ * it later reads.
+ */
+int64_t orthrus_noalloc_scratch_bytes(void);
+orthrus_status orthrus_consensus_commit_noalloc(orthrus_ctx *ctx, const orthrus_params *p,
+                                                const float *ar_logits, const int32_t *draft_tokens,
+                                                const void *k_blk_ar, const void *v_blk_ar,
+                                                void *k_pool, void *v_pool,
+                                                const int32_t *page_table, int32_t *seq_lens,
+                                                int32_t *accept_len, int32_t *num_committed,
+                                                int32_t *out_tokens, int32_t *next_anchor, void *stream);
+
+/*
  * Lossless consensus for temperature T > 0 and commit — Section 3.3, the sentence on diverse
  * generation: exact rejection sampling that aligns the diffusion view's drafts with the AR
  * distribution.  The accept/replace rule is the published speculative-sampling rule the paper cites:

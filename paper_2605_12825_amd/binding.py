@@ -31,6 +31,7 @@ EXPORTED = [
     "orthrus_graph_begin", "orthrus_graph_end", "orthrus_graph_launch", "orthrus_graph_destroy",
     "orthrus_attn_timing", "orthrus_attn_timing_read", "orthrus_attn_timing_samples", "orthrus_last_device_error",
     "orthrus_attn_num_splits_on", "orthrus_attn_workspace_bytes_on", "orthrus_build_id", "orthrus_kv_stream_probe",
+    "orthrus_noalloc_scratch_bytes", "orthrus_consensus_commit_noalloc",
 ]
 
 
@@ -123,6 +124,11 @@ def _load() -> ctypes.CDLL:
     lib.orthrus_attn_num_splits_on.argtypes = [vp, pp]
     lib.orthrus_attn_workspace_bytes_on.restype = ctypes.c_int64
     lib.orthrus_attn_workspace_bytes_on.argtypes = [vp, pp]
+    lib.orthrus_noalloc_scratch_bytes.restype = ctypes.c_int64
+    lib.orthrus_noalloc_scratch_bytes.argtypes = []
+    lib.orthrus_consensus_commit_noalloc.restype = ctypes.c_int
+    lib.orthrus_consensus_commit_noalloc.argtypes = [vp, pp, vp, i32p, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p,
+                                                     i32p, vp]
     lib.orthrus_kv_stream_probe.restype = ctypes.c_int
     lib.orthrus_kv_stream_probe.argtypes = [vp, pp, vp, vp, i32p, i32p, vp]
     return lib
@@ -241,6 +247,23 @@ def orthrus_consensus_commit(ctx, p: orthrus_params, ar_logits, draft_tokens, k_
                                        _stream_handle(stream))
     if check and st != ORTHRUS_OK:
         raise OrthrusError(st, "orthrus_consensus_commit")
+    return st
+
+
+def orthrus_noalloc_scratch_bytes() -> int:
+    return int(_lib.orthrus_noalloc_scratch_bytes())
+
+
+def orthrus_consensus_commit_noalloc(ctx, p: orthrus_params, ar_logits, draft_tokens, k_blk_ar, v_blk_ar, k_pool,
+                                     v_pool, page_table, seq_lens, accept_len, num_committed, out_tokens,
+                                     next_anchor, stream=None, check: bool = True) -> int:
+    st = _lib.orthrus_consensus_commit_noalloc(ctx, ctypes.byref(p), _ptr(ar_logits), _ptr(draft_tokens),
+                                               _ptr(k_blk_ar), _ptr(v_blk_ar), _ptr(k_pool), _ptr(v_pool),
+                                               _ptr(page_table), _ptr(seq_lens), _ptr(accept_len),
+                                               _ptr(num_committed), _ptr(out_tokens), _ptr(next_anchor),
+                                               _stream_handle(stream))
+    if check and st != ORTHRUS_OK:
+        raise OrthrusError(st, "orthrus_consensus_commit_noalloc")
     return st
 
 

@@ -247,6 +247,8 @@ orthrus_status orthrus_create(orthrus_ctx **out, int device)
     c->err_word = nullptr;
     if (hipMalloc((void **)&c->err_word, kCtxWords * sizeof(int32_t)) != hipSuccess) { delete c; return ORTHRUS_EHIP; }
     if (hipMemset(c->err_word, 0, kCtxWords * sizeof(int32_t)) != hipSuccess) { hipFree(c->err_word); delete c; return ORTHRUS_EHIP; }
+    // address of this device's copy of the static scratch array (allocation-free entry point)
+    if (orthrus::consensus_scratch_init(device) != hipSuccess) { hipFree(c->err_word); delete c; return ORTHRUS_EHIP; }
     *out = c;
     return ORTHRUS_OK;
 }
@@ -545,6 +547,27 @@ orthrus_status orthrus_consensus_commit(orthrus_ctx *ctx, const orthrus_params *
     return consensus_commit_impl(ctx, p, ar_logits, draft_tokens, k_blk_ar, v_blk_ar, k_pool, v_pool, page_table,
                                  seq_lens, accept_len, num_committed, out_tokens, next_anchor, workspace,
                                  workspace_bytes, stream);
+}
+
+int64_t orthrus_noalloc_scratch_bytes(void) { return (int64_t)orthrus::consensus_scratch_bytes(); }
+
+orthrus_status orthrus_consensus_commit_noalloc(orthrus_ctx *ctx, const orthrus_params *p,
+                                                const float *ar_logits, const int32_t *draft_tokens,
+                                                const void *k_blk_ar, const void *v_blk_ar,
+                                                void *k_pool, void *v_pool,
+                                                const int32_t *page_table, int32_t *seq_lens,
+                                                int32_t *accept_len, int32_t *num_committed,
+                                                int32_t *out_tokens, int32_t *next_anchor, void *stream)
+{
+    if (!ctx) return ORTHRUS_EINVAL;
+    // the device address of this GPU's static scratch array, looked up when the context was created
+    void *ws = orthrus::consensus_scratch(ctx->device);
+    if (!ws) return ORTHRUS_EHIP;
+    // a problem whose workspace does not fit the fixed array comes back as ORTHRUS_EWORKSPACE from the
+    // shared size check, before anything is launched
+    return consensus_commit_impl(ctx, p, ar_logits, draft_tokens, k_blk_ar, v_blk_ar, k_pool, v_pool, page_table,
+                                 seq_lens, accept_len, num_committed, out_tokens, next_anchor, ws,
+                                 orthrus::consensus_scratch_bytes(), stream);
 }
 
 int64_t orthrus_sampling_workspace_bytes(const orthrus_params *p)

@@ -21,9 +21,46 @@
 // how the scan is split.
 #include "orthrus_internal.h"
 
+#include <mutex>
+
 namespace orthrus {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// ---- device-resident scratch of the allocation-free entry point (orthrus_consensus_commit_noalloc)
+// One fixed array per GPU, held until the process ends; it takes the place of the caller's workspace
+// (chunk argmax pairs and the per-sequence commit record).  Every entry it uses is written by the
+// call's first kernels before anything reads it, so nothing has to start at zero.  Host code never
+// passes the array's name to a kernel: the name is only a handle for hipGetSymbolAddress, and each
+// device has its own copy at its own address, looked up once with that device current.
+constexpr size_t kScratchBytes = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+size_t consensus_scratch_bytes() { return kScratchBytes; }
+
+hipError_t consensus_scratch_init(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device]) return hipSuccess;
+    void *ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));  // the current device's copy
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = ptr;
+    return hipSuccess;
+}
+
+void *consensus_scratch(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    return g_scratch_ptr[device];
+}
 
 constexpr int kChunkElems = 8192;  // floats per (row, chunk) workgroup: 32 KiB
 int consensus_chunk_elems() { return kChunkElems; }

@@ -138,6 +138,11 @@ hipError_t launch_prefill_attn(const AttnArgs &a, int head_dim, hipStream_t stre
 hipError_t launch_consensus(const ConsensusArgs &a, hipStream_t stream);
 hipError_t launch_sampling_consensus(const SamplingArgs &a, hipStream_t stream);
 int consensus_chunk_elems();
+// Static device scratch of the allocation-free consensus entry point: looked up once per device (with
+// that device current), then used through the returned device address only.
+hipError_t consensus_scratch_init(int device);
+void *consensus_scratch(int device);
+size_t consensus_scratch_bytes();
 // Measurement helper: the attention call's own K/V stream with idle compute waves (same grid, same
 // partition, same loader, no arithmetic, nothing written).
 hipError_t launch_kv_stream_probe(const AttnArgs &a, const AttnPlan &plan, int head_dim, hipStream_t stream,
