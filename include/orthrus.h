@@ -67,8 +67,8 @@ typedef enum {
  *
  * Supported by the kernels: head_dim in {64, 128}; page_size a power of two >= 16;
  * 1 <= block_k <= 32; num_q_heads a multiple of num_kv_heads with
- * (num_q_heads / num_kv_heads) * block_k <= 256; sm_scale > 0; every pool stride a multiple
- * of 8 elements (16-byte rows).  Anything else that is otherwise consistent returns
+ * (num_q_heads / num_kv_heads) * block_k <= 256; sm_scale > 0; every pool stride and every block-input
+ * stride a multiple of 8 elements (16-byte rows), head strides >= d.  Anything else that is otherwise consistent returns
  * ORTHRUS_EUNSUPPORTED.
  */
 typedef struct {
@@ -96,6 +96,21 @@ typedef struct {
     int64_t pool_stride_page;
     int64_t pool_stride_head;
     int64_t pool_stride_tok;
+    /* element strides of the block inputs, so that they can be read where the projections left them (for
+       instance inside the output of one fused Q/K/V projection, [B*K, (H_q + 2 H_kv) * d], with the three
+       pointers set to its Q, K and V column ranges) instead of being copied into dense tensors first.
+       0 means dense: q_stride_row = H_q * d, q_stride_head = d, blk_stride_row = H_kv * d,
+       blk_stride_head = d, blk_stride_layer = B * K * blk_stride_row.
+       q element (b, i, h, c) is at (b*K + i) * q_stride_row + h * q_stride_head + c;
+       k_blk / v_blk element (layer, b, i, g, c) is at
+       layer * blk_stride_layer + (b*K + i) * blk_stride_row + g * blk_stride_head + c
+       (attention reads layer 0 of the pointer it is given; the commit reads every layer).
+       Outputs are always dense.  orthrus_prefill_attn ignores these fields (its inputs are dense). */
+    int64_t q_stride_row;
+    int64_t q_stride_head;
+    int64_t blk_stride_row;
+    int64_t blk_stride_head;
+    int64_t blk_stride_layer;
 } orthrus_params;
 
 /* Creates a context on HIP device `device` (allocates one small device error word).  [host] out. */
@@ -144,6 +159,9 @@ const char *orthrus_build_id(void);
  *   q        [dev] bf16 [B, K, H_q, d]      queries of the block (post-projection, post-RoPE)
  *   k_blk    [dev] bf16 [B, K, H_kv, d]     the block's own keys for this view
  *   v_blk    [dev] bf16 [B, K, H_kv, d]     the block's own values for this view
+ *            (these three dense by default, or strided views: q_stride_* / blk_stride_* in params; the
+ *            block of Section 3.1, anchor + K-1 mask positions for the diffusion view, anchor + drafts
+ *            for the AR view, is read where its projections were written)
  *   k_pool   [dev] bf16 paged cache, strides in params (layer 0 is used)
  *   v_pool   [dev] bf16 same strides
  *   page_table [dev] int32 [B, max_pages_per_seq]; entry j maps tokens j*P .. j*P+P-1
@@ -181,7 +199,8 @@ orthrus_status orthrus_dual_view_attn(orthrus_ctx *ctx, const orthrus_params *p,
  *
  *   ar_logits    [dev] fp32 [B, K, V]      row k is conditioned on the anchor and drafts 0..k-1
  *   draft_tokens [dev] int32 [B, K]        values outside [0, V) never match
- *   k_blk_ar, v_blk_ar [dev] bf16 [num_layers, B, K, H_kv, d], or both NULL: consensus only
+ *   k_blk_ar, v_blk_ar [dev] bf16 [num_layers, B, K, H_kv, d] (dense, or strided by blk_stride_* in
+ *                                           params), or both NULL: consensus only
  *                                           (pools, page_table and seq_lens are then not touched)
  *   k_pool, v_pool [dev] bf16, updated in place; page_table [dev] as above
  *   seq_lens     [dev] int32 [B], updated in place

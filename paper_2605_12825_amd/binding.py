@@ -45,6 +45,8 @@ class orthrus_params(ctypes.Structure):
         ("sm_scale", ctypes.c_float), ("num_pages", ctypes.c_int64),
         ("pool_stride_layer", ctypes.c_int64), ("pool_stride_page", ctypes.c_int64),
         ("pool_stride_head", ctypes.c_int64), ("pool_stride_tok", ctypes.c_int64),
+        ("q_stride_row", ctypes.c_int64), ("q_stride_head", ctypes.c_int64), ("blk_stride_row", ctypes.c_int64),
+        ("blk_stride_head", ctypes.c_int64), ("blk_stride_layer", ctypes.c_int64),
     ]
 
 
@@ -368,8 +370,9 @@ def orthrus_last_device_error(ctx, stream=None) -> int:
 
 def make_params(*, batch, num_q_heads, num_kv_heads, head_dim, block_k, page_size, max_pages_per_seq, max_seq_len,
                 num_pages, num_splits=0, num_layers=1, vocab=0, sm_scale=None, pool_stride_layer=None,
-                pool_stride_page=None, pool_stride_head=None, pool_stride_tok=None) -> orthrus_params:
-    """Fills orthrus_params; pool strides default to the [pages, H_kv, P, d] layout."""
+                pool_stride_page=None, pool_stride_head=None, pool_stride_tok=None, q_stride_row=0, q_stride_head=0,
+                blk_stride_row=0, blk_stride_head=0, blk_stride_layer=0) -> orthrus_params:
+    """Fills orthrus_params; pool strides default to the [pages, H_kv, P, d] layout, block inputs to dense."""
     p = orthrus_params()
     p.batch, p.num_q_heads, p.num_kv_heads, p.head_dim = batch, num_q_heads, num_kv_heads, head_dim
     p.block_k, p.page_size, p.max_pages_per_seq, p.max_seq_len = block_k, page_size, max_pages_per_seq, max_seq_len
@@ -380,4 +383,6 @@ def make_params(*, batch, num_q_heads, num_kv_heads, head_dim, block_k, page_siz
     p.pool_stride_head = page_size * head_dim if pool_stride_head is None else pool_stride_head
     p.pool_stride_page = num_kv_heads * page_size * head_dim if pool_stride_page is None else pool_stride_page
     p.pool_stride_layer = num_pages * p.pool_stride_page if pool_stride_layer is None else pool_stride_layer
+    p.q_stride_row, p.q_stride_head = q_stride_row, q_stride_head
+    p.blk_stride_row, p.blk_stride_head, p.blk_stride_layer = blk_stride_row, blk_stride_head, blk_stride_layer
     return p

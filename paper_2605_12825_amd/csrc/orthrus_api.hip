@@ -76,6 +76,14 @@ orthrus_status check_params(const orthrus_params *p, bool need_attn, bool need_c
         if ((p->pool_stride_page | p->pool_stride_head | p->pool_stride_tok | p->pool_stride_layer) & 7)
             return ORTHRUS_EUNSUPPORTED;
         if (p->pool_stride_tok < p->head_dim) return ORTHRUS_EINVAL;
+        // block-input strides: 0 = dense, else 16-byte multiples that keep rows and heads apart
+        if ((p->q_stride_row | p->q_stride_head | p->blk_stride_row | p->blk_stride_head | p->blk_stride_layer) & 7)
+            return ORTHRUS_EUNSUPPORTED;
+        if (p->q_stride_row < 0 || p->q_stride_head < 0 || p->blk_stride_row < 0 || p->blk_stride_head < 0 ||
+            p->blk_stride_layer < 0)
+            return ORTHRUS_EINVAL;
+        if ((p->q_stride_head && p->q_stride_head < p->head_dim) || (p->blk_stride_head && p->blk_stride_head < p->head_dim))
+            return ORTHRUS_EINVAL;
     }
     if (p->block_k > 32) return ORTHRUS_EUNSUPPORTED;
     if (need_attn) {
@@ -151,6 +159,10 @@ orthrus::AttnArgs decode_attn_args(const orthrus_ctx *ctx, const orthrus_params 
     a.old_lens = nullptr; a.new_lens = nullptr; a.max_new = 0;
     a.stride_page = p->pool_stride_page; a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok;
     a.num_pages = p->num_pages;
+    a.q_stride_head = p->q_stride_head ? p->q_stride_head : p->head_dim;
+    a.q_stride_row = p->q_stride_row ? p->q_stride_row : (int64_t)p->num_q_heads * p->head_dim;
+    a.blk_stride_head = p->blk_stride_head ? p->blk_stride_head : p->head_dim;
+    a.blk_stride_row = p->blk_stride_row ? p->blk_stride_row : (int64_t)p->num_kv_heads * p->head_dim;
     a.batch = p->batch; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
     a.group = p->num_q_heads / p->num_kv_heads; a.block_k = p->block_k; a.rows = plan.rows;
     a.page_shift = log2_exact(p->page_size); a.max_pages_per_seq = p->max_pages_per_seq;
@@ -206,6 +218,9 @@ static orthrus_status consensus_commit_impl(orthrus_ctx *ctx, const orthrus_para
     a.err_word = ctx->err_word;
     a.stride_layer = p->pool_stride_layer; a.stride_page = p->pool_stride_page;
     a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok; a.num_pages = p->num_pages;
+    a.blk_stride_head = p->blk_stride_head ? p->blk_stride_head : p->head_dim;
+    a.blk_stride_row = p->blk_stride_row ? p->blk_stride_row : (int64_t)p->num_kv_heads * p->head_dim;
+    a.blk_stride_layer = p->blk_stride_layer ? p->blk_stride_layer : (int64_t)p->batch * p->block_k * a.blk_stride_row;
     a.batch = p->batch; a.block_k = p->block_k; a.vocab = p->vocab; a.num_layers = p->num_layers;
     a.num_kv_heads = p->num_kv_heads; a.head_dim = p->head_dim;
     a.page_shift = do_commit ? log2_exact(p->page_size) : 0; a.max_pages_per_seq = p->max_pages_per_seq;
@@ -388,6 +403,8 @@ orthrus_status orthrus_prefill_attn(orthrus_ctx *ctx, const orthrus_params *p, i
     a.old_lens = f.old_lens; a.new_lens = f.new_lens; a.max_new = max_new_tokens;
     a.stride_page = p->pool_stride_page; a.stride_head = p->pool_stride_head; a.stride_tok = p->pool_stride_tok;
     a.num_pages = p->num_pages;
+    a.q_stride_head = p->head_dim; a.q_stride_row = (int64_t)p->num_q_heads * p->head_dim;
+    a.blk_stride_head = p->head_dim; a.blk_stride_row = (int64_t)p->num_kv_heads * p->head_dim;
     a.batch = p->batch; a.num_q_heads = p->num_q_heads; a.num_kv_heads = p->num_kv_heads;
     a.group = group; a.block_k = 32; a.rows = 32 * group;
     a.page_shift = f.page_shift; a.max_pages_per_seq = p->max_pages_per_seq;
@@ -629,6 +646,9 @@ orthrus_status orthrus_sampling_consensus_commit(orthrus_ctx *ctx, const orthrus
     c.err_word = ctx->err_word;
     c.stride_layer = p->pool_stride_layer; c.stride_page = p->pool_stride_page;
     c.stride_head = p->pool_stride_head; c.stride_tok = p->pool_stride_tok; c.num_pages = p->num_pages;
+    c.blk_stride_head = p->blk_stride_head ? p->blk_stride_head : p->head_dim;
+    c.blk_stride_row = p->blk_stride_row ? p->blk_stride_row : (int64_t)p->num_kv_heads * p->head_dim;
+    c.blk_stride_layer = p->blk_stride_layer ? p->blk_stride_layer : (int64_t)p->batch * p->block_k * c.blk_stride_row;
     c.batch = p->batch; c.block_k = p->block_k; c.vocab = p->vocab; c.num_layers = p->num_layers;
     c.num_kv_heads = p->num_kv_heads; c.head_dim = p->head_dim;
     c.page_shift = do_commit ? log2_exact(p->page_size) : 0; c.max_pages_per_seq = p->max_pages_per_seq;

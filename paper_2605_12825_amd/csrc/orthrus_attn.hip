@@ -425,7 +425,7 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
                 const int u = id % NI;
                 const uint16_t *blk = id < NI ? a.k_blk : a.v_blk;
                 const int tok = u * RPI + ld_tok;
-                const int64_t off = (((int64_t)b * K + min(tok, K - 1)) * a.num_kv_heads + g) * D +
+                const int64_t off = ((int64_t)b * K + min(tok, K - 1)) * a.blk_stride_row + (int64_t)g * a.blk_stride_head +
                                     ((ld_ch ^ xm<CH>(ld_tok)) << 3);
                 dma16(nt, blk + off, dst + (id < NI ? 0 : TILE_B) + u * GS);
             }
@@ -511,7 +511,7 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
         if (row_ok) {
             const int i = ridx / G, hl = ridx - i * G;
             irow = i;
-            const uint16_t *qp = a.q + ((row_base + i) * a.num_q_heads + (int64_t)g * G + hl) * D;
+            const uint16_t *qp = a.q + (row_base + i) * a.q_stride_row + ((int64_t)g * G + hl) * a.q_stride_head;
 #pragma unroll
             for (int kk = 0; kk < KSTEPS; ++kk) qf[kk].u = *(const uint4 *)(qp + kk * 16 + h * 8);
         } else {
@@ -647,7 +647,8 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const f32x4 v = {o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]};
-                    __builtin_nontemporal_store(v, &po[(db * 4 + r4) * 64]);
+                    if (a.kv_nt) __builtin_nontemporal_store(v, &po[(db * 4 + r4) * 64]);
+                    else po[(db * 4 + r4) * 64] = v;
                 }
             if (h == 0) ((float2 *)a.part_ml)[slot * 32 + col] = make_float2(m_run, l_run);
         }

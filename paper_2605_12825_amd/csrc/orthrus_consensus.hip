@@ -151,12 +151,20 @@ __global__ void __launch_bounds__(256) accept_commit_kernel(const ConsensusArgs 
     const int b = blockIdx.x, tid = threadIdx.x;
     const int K = a.block_k;
     __shared__ int s_L, s_m;
-    __shared__ int s_am[32];
+    __shared__ int s_am[32], s_pg[32];
+    const int wave = tid >> 6, lane = tid & 63;
+    // ---- loads that do not depend on the argmaxes go out first (first wave): the drafts, the length
+    // and the page ids of the K positions that may be appended
+    int draft = -1;
+    CommitProbe probe = {0, -1};
+    if (wave == 0) {
+        if (lane < K) draft = a.draft_tokens[(int64_t)b * K + lane];
+        if (a.do_commit) probe = commit_probe(a, b, lane);
+    }
     // ---- row argmaxes: wave w finishes rows w, w+4, ...; a lane takes the chunk pairs lane, lane+64, ...
     // All loads of a wave's rows go out before the first reduction, so the phase costs one memory round
     // trip, not one per chunk.  A lane without a chunk holds (-inf, INT_MAX), which every real pair outranks.
     {
-        const int wave = tid >> 6, lane = tid & 63;
         constexpr int kRowsPerWave = 8;  // block_k <= 32 rows over 4 waves
         float bv[kRowsPerWave];
         int bi[kRowsPerWave];
@@ -185,13 +193,12 @@ __global__ void __launch_bounds__(256) accept_commit_kernel(const ConsensusArgs 
     }
     __syncthreads();
     // ---- accept: the first wave, lane k < K owns block row k of sequence b
-    if (tid < 64) {
-        const int lane = tid;
+    if (wave == 0) {
         int am = -1;
         bool match = false;
         if (lane < K) {
             am = s_am[lane];
-            match = a.draft_tokens[(int64_t)b * K + lane] == am;
+            match = draft == am;
         }
         // accepted prefix = run of matching rows starting at row 0
         const unsigned long long mism = ~__ballot(match);           // lanes >= K never match
@@ -200,20 +207,22 @@ __global__ void __launch_bounds__(256) accept_commit_kernel(const ConsensusArgs 
         if (lane < K) a.out_tokens[(int64_t)b * K + lane] = lane < m ? am : -1;
         const int anchor = __shfl(am, m - 1);
         int committed = m;
-        int L = 0;
-        if (a.do_commit) committed = check_and_bump(a, b, lane, m, &L);
+        if (a.do_commit) {
+            committed = commit_decide(a, b, lane, m, probe);
+            if (lane < K) s_pg[lane] = probe.pg;
+        }
         if (lane == 0) {
             a.accept_len[b] = n_acc;
             a.num_committed[b] = committed;
             a.next_anchor[b] = anchor;
-            s_L = L;
+            s_L = probe.L;
             s_m = a.do_commit ? committed : 0;
         }
     }
     __syncthreads();
     // ---- commit: the whole workgroup copies the appended rows when there are few layers
     if (a.do_commit && a.num_layers <= kInlineLayers && s_m > 0)
-        for (int layer = 0; layer < a.num_layers; ++layer) append_rows(a, b, layer, s_L, s_m, tid, 256);
+        for (int layer = 0; layer < a.num_layers; ++layer) append_rows(a, b, layer, s_L, s_m, tid, 256, s_pg);
 }
 
 // The same copy as its own launch: grid (sequence, layer).

@@ -33,6 +33,9 @@ struct AttnArgs {
     const int32_t *old_lens, *new_lens;
     int max_new;
     int64_t stride_page, stride_head, stride_tok, num_pages;
+    // block inputs: elements between consecutive rows (b*K + i) and heads of q, and of k_blk / v_blk
+    // (prefill: of q and of the new K/V rows, always dense)
+    int64_t q_stride_row, q_stride_head, blk_stride_row, blk_stride_head;
     int batch, num_q_heads, num_kv_heads, group, block_k, rows;
     int page_shift, max_pages_per_seq, max_seq_len, chunk_tokens, num_splits, view;
     int bal_wgs;  // balanced partition: workgroups of the split launch (0 otherwise)
@@ -52,6 +55,7 @@ struct ConsensusArgs {
     int32_t *commit_info;  // [B][2]: length before the step, rows to append (0 = none)
     int32_t *err_word;
     int64_t stride_layer, stride_page, stride_head, stride_tok, num_pages;
+    int64_t blk_stride_layer, blk_stride_row, blk_stride_head;  // of k_blk_ar / v_blk_ar
     int batch, block_k, vocab, num_layers, num_kv_heads, head_dim;
     int page_shift, max_pages_per_seq, chunks, chunk_elems, do_commit;
 };
@@ -69,53 +73,82 @@ struct SamplingArgs {
 // ---- commit helpers shared by the greedy and the sampling consensus kernels (device code)
 #if defined(__HIPCC__)
 // Copy rows 0..m-1 of the AR view's block K/V of (sequence b, layer) to token positions L..L+m-1 of the
-// pools (Fig. 2(b): only the accepted tokens' K/V enters the shared cache), as 16-byte chunks.
-__device__ __forceinline__ void append_rows(const ConsensusArgs &a, int b, int layer, int L, int m, int tid, int nthreads)
+// pools (Fig. 2(b): only the accepted tokens' K/V enters the shared cache), as 16-byte chunks.  `pages`
+// (LDS or NULL) holds the page id of position L+k at index k when the caller has fetched them already.
+__device__ __forceinline__ void append_rows(const ConsensusArgs &a, int b, int layer, int L, int m, int tid, int nthreads,
+                                            const int *pages = nullptr)
 {
     const int K = a.block_k, H = a.num_kv_heads, d = a.head_dim;
     const int cpr = d / 8;  // 16-byte chunks per row
     const int per_tok = H * cpr;
     const int total = m * per_tok;
     const int P = 1 << a.page_shift;
-    for (int e = tid; e < total; e += nthreads) {
+    // four chunks of each pool per thread are in flight before the first store (the compiler may not move
+    // a load above a store to the pools): the copy costs a memory round trip per four chunks, not per chunk
+    constexpr int kBatch = 4;
+    auto src_of = [&](int e) __attribute__((always_inline)) {
+        const int k = e / per_tok, rem = e - k * per_tok;
+        const int g = rem / cpr, ch = rem - g * cpr;
+        return (int64_t)layer * a.blk_stride_layer + ((int64_t)b * K + k) * a.blk_stride_row + (int64_t)g * a.blk_stride_head + ch * 8;
+    };
+    auto dst_of = [&](int e) __attribute__((always_inline)) {
         const int k = e / per_tok, rem = e - k * per_tok;
         const int g = rem / cpr, ch = rem - g * cpr;
         const int pos = L + k;
-        const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + (pos >> a.page_shift)];
-        const int64_t src = ((((int64_t)layer * a.batch + b) * K + k) * H + g) * d + ch * 8;
-        const int64_t dst = (int64_t)layer * a.stride_layer + (int64_t)pg * a.stride_page +
-                            (int64_t)g * a.stride_head + (int64_t)(pos & (P - 1)) * a.stride_tok + ch * 8;
-        *(uint4 *)(a.k_pool + dst) = *(const uint4 *)(a.k_blk_ar + src);
-        *(uint4 *)(a.v_pool + dst) = *(const uint4 *)(a.v_blk_ar + src);
+        const int pg = pages ? pages[k] : a.page_table[(int64_t)b * a.max_pages_per_seq + (pos >> a.page_shift)];
+        return (int64_t)layer * a.stride_layer + (int64_t)pg * a.stride_page + (int64_t)g * a.stride_head +
+               (int64_t)(pos & (P - 1)) * a.stride_tok + ch * 8;
+    };
+    for (int e0 = tid; e0 < total; e0 += nthreads * kBatch) {
+        const int e1 = e0 + nthreads, e2 = e0 + 2 * nthreads, e3 = e0 + 3 * nthreads;
+        uint4 k0, v0, k1, v1, k2, v2, k3, v3;
+        k0 = *(const uint4 *)(a.k_blk_ar + src_of(e0)); v0 = *(const uint4 *)(a.v_blk_ar + src_of(e0));
+        k1 = v1 = k2 = v2 = k3 = v3 = make_uint4(0, 0, 0, 0);
+        if (e1 < total) { k1 = *(const uint4 *)(a.k_blk_ar + src_of(e1)); v1 = *(const uint4 *)(a.v_blk_ar + src_of(e1)); }
+        if (e2 < total) { k2 = *(const uint4 *)(a.k_blk_ar + src_of(e2)); v2 = *(const uint4 *)(a.v_blk_ar + src_of(e2)); }
+        if (e3 < total) { k3 = *(const uint4 *)(a.k_blk_ar + src_of(e3)); v3 = *(const uint4 *)(a.v_blk_ar + src_of(e3)); }
+        { const int64_t t = dst_of(e0); *(uint4 *)(a.k_pool + t) = k0; *(uint4 *)(a.v_pool + t) = v0; }
+        if (e1 < total) { const int64_t t = dst_of(e1); *(uint4 *)(a.k_pool + t) = k1; *(uint4 *)(a.v_pool + t) = v1; }
+        if (e2 < total) { const int64_t t = dst_of(e2); *(uint4 *)(a.k_pool + t) = k2; *(uint4 *)(a.v_pool + t) = v2; }
+        if (e3 < total) { const int64_t t = dst_of(e3); *(uint4 *)(a.k_pool + t) = k3; *(uint4 *)(a.v_pool + t) = v3; }
     }
+    static_assert(kBatch == 4, "the loop body above is written out for four chunks");
 }
 
-// Run by the first wave of a sequence's workgroup once it knows m, the number of rows to append: checks
-// that positions L..L+m-1 (L = seq_lens[b]) are mapped, then either bumps the length or flags the
-// capacity error and leaves the sequence alone.  Records (L, rows to append) for the copy.  Returns the
-// rows that will be appended (m or 0); *L_out = L.  Every lane of the wave must call it.
-__device__ __forceinline__ int check_and_bump(const ConsensusArgs &a, int b, int lane, int m, int *L_out)
+// What lane k < K of a sequence's first wave learns about token position L + k (L = seq_lens[b]) before
+// the number of rows to append is known: fetched at the start of the kernel, so that these dependent
+// loads (length, then page id) run next to the argmax reductions instead of after them.
+struct CommitProbe {
+    int L;    // length before the step (same in every lane)
+    int pg;   // page id of position L + lane, -1 if the slot lies beyond the page table
+};
+__device__ __forceinline__ CommitProbe commit_probe(const ConsensusArgs &a, int b, int lane)
 {
-    const int L = a.seq_lens[b];
-    bool bad = false;
-    if (lane < m) {
-        const int pos = L + lane;
-        const int slot = pos >> a.page_shift;
-        if (L < 0 || slot >= a.max_pages_per_seq) bad = true;
-        else {
-            const int pg = a.page_table[(int64_t)b * a.max_pages_per_seq + slot];
-            bad = pg < 0 || pg >= a.num_pages;
-        }
+    CommitProbe p;
+    p.L = a.seq_lens[b];
+    p.pg = -1;
+    if (lane < a.block_k && p.L >= 0) {
+        const int slot = (p.L + lane) >> a.page_shift;
+        if (slot < a.max_pages_per_seq) p.pg = a.page_table[(int64_t)b * a.max_pages_per_seq + slot];
     }
+    return p;
+}
+
+// Run by the first wave once it knows m, the number of rows to append: positions L..L+m-1 must be mapped;
+// then the length is bumped, else the capacity error is flagged and the sequence left alone.  Records
+// (L, rows to append) for a later copy launch.  Returns the rows that will be appended (m or 0).  Every
+// lane of the wave must call it.
+__device__ __forceinline__ int commit_decide(const ConsensusArgs &a, int b, int lane, int m, const CommitProbe &p)
+{
+    const bool bad = lane < m && (p.pg < 0 || p.pg >= a.num_pages);
     const bool any_bad = __ballot(bad) != 0ull;
     const int committed = any_bad ? 0 : m;
     if (lane == 0) {
-        a.commit_info[b * 2] = L;
+        a.commit_info[b * 2] = p.L;
         a.commit_info[b * 2 + 1] = committed;
         if (any_bad) atomicExch(a.err_word, -4);
-        else a.seq_lens[b] = L + m;
+        else a.seq_lens[b] = p.L + m;
     }
-    *L_out = L;
     return committed;
 }
 #endif

@@ -227,8 +227,13 @@ __global__ void __launch_bounds__(256) sample_commit_kernel(const SamplingArgs a
     const int b = blockIdx.x, tid = threadIdx.x;
     const int K = c.block_k, chunks = c.chunks;
     __shared__ int s_L, s_m;
+    __shared__ int s_pg[32];
     if (tid < 64) {
         const int lane = tid;
+        // the length and the page ids of the K positions that may be appended do not depend on the
+        // decisions: their loads go out first
+        CommitProbe probe = {0, -1};
+        if (c.do_commit) probe = commit_probe(c, b, lane);
         float lp, lq;
         const int j = first_rejected(a, b, lane, lp, lq);
         int repl = -1;
@@ -257,8 +262,12 @@ __global__ void __launch_bounds__(256) sample_commit_kernel(const SamplingArgs a
             c.out_tokens[(int64_t)b * K + lane] = lane < m ? t : -1;
         }
         const int last_tok = (j < K) ? repl : c.draft_tokens[(int64_t)b * K + K - 1];
-        int committed = m, L = 0;
-        if (c.do_commit) committed = check_and_bump(c, b, lane, m, &L);
+        int committed = m;
+        const int L = probe.L;
+        if (c.do_commit) {
+            committed = commit_decide(c, b, lane, m, probe);
+            if (lane < K) s_pg[lane] = probe.pg;
+        }
         if (lane == 0) {
             c.accept_len[b] = j;
             c.num_committed[b] = committed;
@@ -269,7 +278,7 @@ __global__ void __launch_bounds__(256) sample_commit_kernel(const SamplingArgs a
     }
     __syncthreads();
     if (c.do_commit && c.num_layers <= kSInlineLayers && s_m > 0)
-        for (int layer = 0; layer < c.num_layers; ++layer) append_rows(c, b, layer, s_L, s_m, tid, 256);
+        for (int layer = 0; layer < c.num_layers; ++layer) append_rows(c, b, layer, s_L, s_m, tid, 256, s_pg);
 }
 
 __global__ void __launch_bounds__(256) sample_commit_layers_kernel(const SamplingArgs a)

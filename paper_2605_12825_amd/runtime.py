@@ -30,7 +30,7 @@ class DecodeStep:
 
     def __init__(self, *, batch, num_q_heads, num_kv_heads, head_dim, block_k, page_size, max_pages_per_seq,
                  max_seq_len, num_pages, vocab=0, num_layers=1, num_splits=0, sm_scale=None, device=0,
-                 pool_strides=None, min_seq_len_bound=None):
+                 pool_strides=None, min_seq_len_bound=None, block_strides=None):
         if not torch.cuda.is_available():
             raise RuntimeError("paper_2605_12825_amd needs a HIP device; there is no CPU path")
         self.device = torch.device("cuda", device)
@@ -38,6 +38,9 @@ class DecodeStep:
         if pool_strides is not None:
             kw = dict(pool_stride_layer=pool_strides[0], pool_stride_page=pool_strides[1],
                       pool_stride_head=pool_strides[2], pool_stride_tok=pool_strides[3])
+        if block_strides is not None:   # (q_stride_row, q_stride_head, blk_stride_row, blk_stride_head, blk_stride_layer)
+            kw.update(q_stride_row=block_strides[0], q_stride_head=block_strides[1], blk_stride_row=block_strides[2],
+                      blk_stride_head=block_strides[3], blk_stride_layer=block_strides[4])
         self.params = B.make_params(batch=batch, num_q_heads=num_q_heads, num_kv_heads=num_kv_heads,
                                     head_dim=head_dim, block_k=block_k, page_size=page_size,
                                     max_pages_per_seq=max_pages_per_seq, max_seq_len=max_seq_len,
