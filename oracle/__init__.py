@@ -17,6 +17,14 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "orthrus_oracle.c")
 _LIB = os.path.join(_HERE, "liborthrus_oracle.so")
+# sanitizer builds (CPU test suite): the same source under AddressSanitizer + UndefinedBehaviorSanitizer as a
+# library (selected with ORTHRUS_ORACLE_SANITIZE=1; load it with ASAN_OPTIONS=verify_asan_link_order=0) and
+# as a self-contained driver executable (sanitize_selftest.c)
+_LIB_SAN = os.path.join(_HERE, "liborthrus_oracle_asan.so")
+_SELFTEST_SRC = os.path.join(_HERE, "sanitize_selftest.c")
+_SELFTEST = os.path.join(_HERE, "sanitize_selftest")
+_SAN_FLAGS = ["-O1", "-g", "-std=c11", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+              "-fno-omit-frame-pointer", "-Wall", "-Wextra"]
 
 VIEW_DIFFUSION = 0
 VIEW_AR_VERIFY = 1
@@ -35,10 +43,26 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """The oracle as a shared library under ASan + UBSan (gcc's shared sanitizer runtimes)."""
+    tmp = _LIB_SAN + ".tmp.%d" % os.getpid()
+    subprocess.run(["gcc"] + _SAN_FLAGS + ["-fPIC", "-shared", "-o", tmp, _SRC, "-lm"], check=True)
+    os.replace(tmp, _LIB_SAN)
+    return _LIB_SAN
+
+
+def build_selftest() -> str:
+    """The sanitizer driver executable: oracle + sanitize_selftest.c under ASan + UBSan."""
+    tmp = _SELFTEST + ".tmp.%d" % os.getpid()
+    subprocess.run(["gcc"] + _SAN_FLAGS + ["-o", tmp, _SRC, _SELFTEST_SRC, "-lm"], check=True)
+    os.replace(tmp, _SELFTEST)
+    return _SELFTEST
+
+
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        lib = ctypes.CDLL(build_sanitized() if os.environ.get("ORTHRUS_ORACLE_SANITIZE") == "1" else build())
         i32, i64, f64 = ctypes.c_int, ctypes.c_int64, ctypes.c_double
         p = ctypes.c_void_p
         lib.orthrus_oracle_num_threads.restype = ctypes.c_int

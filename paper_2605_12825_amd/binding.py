@@ -56,8 +56,15 @@ class OrthrusError(RuntimeError):
         super().__init__("%s: %s (%d)" % (where, orthrus_status_string(status), status))
 
 
+def _library_file() -> str:
+    """The built library; ORTHRUS_LIBRARY selects another build of the same sources (the host-UBSan one)."""
+    return os.environ.get("ORTHRUS_LIBRARY") or _build.LIB
+
+
 def _load() -> ctypes.CDLL:
-    if not os.path.exists(_build.LIB):
+    if not os.path.exists(_library_file()):
+        if os.environ.get("ORTHRUS_LIBRARY"):
+            raise ImportError("ORTHRUS_LIBRARY=%s does not exist" % _library_file())
         _build.build_library()   # nothing built yet: build once
     # PyTorch ships its own HIP runtime; load it first so that this library binds to that one.  Two
     # HIP runtimes in one process do not share the GPU: whichever initialises second sees no device.
@@ -65,7 +72,7 @@ def _load() -> ctypes.CDLL:
         import torch  # noqa: F401
     except ImportError:
         pass
-    lib = ctypes.CDLL(_build.LIB)
+    lib = ctypes.CDLL(_library_file())
     # A library older than the sources next to it would silently test yesterday's kernels: its build id is
     # the digest of the sources and flags it was compiled from, so a mismatch means "rebuild".
     lib.orthrus_build_id.restype = ctypes.c_char_p
@@ -73,7 +80,7 @@ def _load() -> ctypes.CDLL:
     built, now = lib.orthrus_build_id().decode(), _build.source_digest()
     if built != now:
         raise ImportError("%s was built from other sources (build id %s, sources %s): rebuild it with "
-                          "`python -m paper_2605_12825_amd.build`" % (_build.LIB, built, now))
+                          "`python -m paper_2605_12825_amd.build`" % (_library_file(), built, now))
     vp, i32p = ctypes.c_void_p, ctypes.c_void_p
     pp = ctypes.POINTER(orthrus_params)
     lib.orthrus_create.restype = ctypes.c_int
@@ -140,7 +147,7 @@ _lib = _load()
 
 
 def library_path() -> str:
-    return _build.LIB
+    return _library_file()
 
 
 def _ptr(t) -> Optional[int]:

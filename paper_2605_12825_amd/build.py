@@ -10,6 +10,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 HEADER = os.path.join(os.path.dirname(_HERE), "include", "orthrus.h")
 LIB = os.path.join(_HERE, "liborthrus.so")
+# the same library with its host code (argument validation, planning, workspace carving) compiled under
+# UndefinedBehaviorSanitizer in trap mode: no sanitizer runtime is needed to load it, undefined behaviour ends the process
+LIB_HOST_UBSAN = os.path.join(_HERE, "liborthrus_hostubsan.so")
+HOST_UBSAN_FLAGS = ["-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fsanitize-trap=undefined",
+                    "-Xarch_host", "-fno-omit-frame-pointer"]
 SOURCES = ["orthrus_api.hip", "orthrus_attn.hip", "orthrus_consensus.hip", "orthrus_sampling.hip",
            "orthrus_prefill.hip"]
 
@@ -39,10 +44,12 @@ def source_digest() -> str:
     return h.hexdigest()[:16]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source into paper_2605_12825_amd/liborthrus.so and return its path."""
-    tag = ".tmp.%d" % os.getpid()
-    flags = HIPCC_FLAGS + ['-DORTHRUS_BUILD_ID="%s"' % source_digest()]
+def build_library(verbose: bool = False, host_ubsan: bool = False) -> str:
+    """Compile every HIP source into paper_2605_12825_amd/liborthrus.so (or, with host_ubsan, into
+    liborthrus_hostubsan.so with the host code under UBSan traps) and return its path."""
+    tag = ".tmp.%d%s" % (os.getpid(), "u" if host_ubsan else "")
+    flags = HIPCC_FLAGS + ['-DORTHRUS_BUILD_ID="%s"' % source_digest()] + (HOST_UBSAN_FLAGS if host_ubsan else [])
+    LIB = LIB_HOST_UBSAN if host_ubsan else globals()["LIB"]
     objs = [os.path.join(_HERE, s.replace(".hip", tag + ".o")) for s in SOURCES]
 
     def compile_one(pair):
@@ -73,4 +80,5 @@ def build_library(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import sys
+    print(build_library(verbose=True, host_ubsan="--host-ubsan" in sys.argv))
