@@ -27,23 +27,28 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E published peak
 N_SETS = 4              # rotating sets of block inputs / logits (fresh data every step, cycled)
 
 
-def measured_traffic(workload, block_k, splits):
+def measured_traffic(workload, block_k, splits, algorithmic_bytes):
     """HBM bytes per attention call from the rocprofv3 --pmc summary committed for this very configuration.
 
     A summary under profiles/ that was made from FETCH_SIZE / WRITE_SIZE runs of this script carries a line
-    `traffic-per-call: workload=<w> block_k=<K> splits=<S> read_bytes=<n> write_bytes=<n>` (counters scaled by
-    what they read for a plain copy of known size).  No such line for the configuration at hand: null.
+    `traffic-per-call: workload=<w> block_k=<K> splits=<S> read_bytes=<n> write_bytes=<n> algorithmic_bytes=<n>`
+    (counters of the split and combine kernels, scaled by what they read for a plain copy of known size, and the
+    algorithmic K/V bytes of a call at the lengths of those counter runs).  The figure returned is that measured /
+    algorithmic ratio applied to this run's algorithmic bytes (the cache grows from step to step).  No such line
+    for the configuration at hand: null.
     """
     import glob
     import re
     for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
         for line in open(path):
             m = re.match(r"\s*traffic-per-call: workload=(\S+) block_k=(\d+) splits=(\S+) read_bytes=(\d+) "
-                         r"write_bytes=(\d+)", line)
-            if m and m.group(1) == workload and int(m.group(2)) == block_k and m.group(3) == str(splits):
-                return {"traffic": int(m.group(4)) + int(m.group(5)),
+                         r"write_bytes=(\d+) algorithmic_bytes=(\d+)", line)
+            if m and m.group(1) == workload and int(m.group(2)) == block_k and m.group(3) == str(splits) \
+                    and int(m.group(6)) > 0:
+                ratio = (int(m.group(4)) + int(m.group(5))) / float(m.group(6))
+                return {"traffic": int(ratio * algorithmic_bytes), "traffic_over_algorithmic": round(ratio, 4),
                         "traffic_source": os.path.relpath(path, ROOT)}
-    return {"traffic": None, "traffic_source": None}
+    return {"traffic": None, "traffic_over_algorithmic": None, "traffic_source": None}
 
 
 def log(*a):
@@ -87,6 +92,9 @@ def parse():
                     help="attach the events to every Nth of those steps only")
     ap.add_argument("--ceiling-launches", type=int, default=50,
                     help="launches of the no-arithmetic K/V stream probe that measure the ceiling")
+    ap.add_argument("--no-prescribed-splits", action="store_true",
+                    help="long workload: skip the side-by-side timing of the 64-split plan the workload names "
+                         "(counter runs, where its launches would be averaged into the same kernel name)")
     ap.add_argument("--pools", type=int, default=0,
                     help="copies of the cache to rotate over (0: 4 for a workload without a commit step, else 1)")
     ap.add_argument("--calibrate-read", action="store_true",
@@ -584,7 +592,7 @@ def main():
                     "combine_kernel": stats(cb) if cb.max() > 0 else None,
                     "mfma": {"flop_per_byte": R, "achieved_tflops": round(tf, 1), "peak_tflops": 2500.0,
                              "frac": round(tf / 2500.0, 4)}}
-        roofline.update(measured_traffic(w.name, K, "balanced" if splits == -1 else step.num_splits))
+        roofline.update(measured_traffic(w.name, K, "balanced" if splits == -1 else step.num_splits, kv_bytes_post))
         extra["attn_split_kernel_us"] = stats(sp)["avg_us"]
         extra["attn_combine_kernel_us"] = stats(cb)["avg_us"]
         extra["attn_call_kernels_us"] = stats(call)["avg_us"]
@@ -604,7 +612,7 @@ def main():
                                        achieved=c["achieved"], frac_of_peak=c["frac"])
             roofline["ceiling_frac"] = round(r_call["achieved"] / c["achieved"], 4)
         # ---- the long workload names 64 splits per sequence: that plan, timed side by side
-        if w.name == "long" and args.block_k == 0 and step.num_splits != 64:
+        if w.name == "long" and args.block_k == 0 and step.num_splits != 64 and not args.no_prescribed_splits:
             s64 = mk_step(64)
             s64.set_max_seq_len(min(cap, int(lens_post.max())))
             for j in range(10):
