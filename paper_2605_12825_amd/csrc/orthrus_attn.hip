@@ -668,8 +668,8 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
 // a unit held by one workgroup was finished by the split kernel.
 //
 // CHUNK = partials merged per round of loads: 8 keeps the registers low for the bandwidth-bound merges
-// of many units with few pieces each; 16 halves the dependent round trips of a latency-bound merge of
-// few units with many splits.
+// of many units with few pieces each; 16 or 32 make the latency-bound merge of few units with many
+// splits a single memory round trip (a second round costs it ~1 us).
 template <int D, int W, int BALANCED = 0, int CHUNK = 8>
 __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
 {
@@ -831,31 +831,40 @@ hipError_t plan_attn(int head_dim, int group, int block_k, int batch, int num_kv
     if (requested_splits > 0) {
         splits = requested_splits;
     } else {
-        // Pick the split count with a small cost model (times in microseconds), using max_seq_len for
-        // every sequence: workgroups run in rounds of `slots`; a round streams at the practical HBM
-        // rate once every CU holds a workgroup; every split beyond the first writes and re-reads an
-        // fp32 partial (rows x d x 4 bytes) and adds the combine launch.
-        const double kRate = 6.0e6;          // bytes per microsecond (practical streaming ceiling)
-        const double kRound = 5.0, kCombine = 8.0;
+        // Pick the split count with a small cost model (times in microseconds, constants measured on
+        // this chip), using max_seq_len for every sequence.  Workgroups run in rounds of `slots`.  A
+        // workgroup needs at least kTile per 32-token tile whatever the stream could deliver (the
+        // loader wave's issue rate and the dependent chain of one tile's products and softmax are
+        // both about that long: what binds when few CUs are busy, e.g. batch 1), and the tiles of all
+        // workgroups of a round together stream no faster than kRate.  Every workgroup costs kWg to
+        // dispatch; every piece beyond a unit's first is an fp32 partial (rows x d x 4 bytes) written
+        // once and read once, and brings the merge launch with it.
+        const double kRate = 7.0e6;      // K/V bytes per microsecond (measured ceiling of the paged stream)
+        const double kPartRate = 6.0e6;  // bytes per microsecond for the partials
+        const double kTile = W <= 4 ? 0.56 : 1.3;  // more than four 32-row blocks: two per SIMD
+        const double kRound = 5.0, kCombine = 4.0, kSplit = 0.12, kWg = 0.008;
         const int64_t slots = (int64_t)num_cus * per_cu;
-        const double row_bytes = 2.0 * head_dim * 2.0;  // K + V bytes per cached token per KV head
+        const double tile_bytes = 32.0 * 2.0 * head_dim * 2.0;  // K + V bytes of one tile of one KV head
         const double part_bytes = 2.0 * plan->rows_padded * head_dim * 4.0;  // written once, read once
         const int max_s = max_seq_len >= 256 ? (max_seq_len / 128 < 64 ? max_seq_len / 128 : 64) : 1;
+        const int tiles = (max_seq_len + 31) / 32;
+        double cost[65];
         double best = 1e300;
-        splits = 1;
         for (int s = 1; s <= max_s; ++s) {
             const int64_t wgs = units * s;
-            const double per_wg = row_bytes * ((double)max_seq_len / s) + (s > 1 ? part_bytes : 0.0);
-            double t = s > 1 ? kCombine : 0.0;
+            const double tiles_per_wg = (double)((tiles + s - 1) / s);
+            double t = s > 1 ? kCombine + kSplit * s : 0.0;  // the merge reads one more partial per output and split
             for (int64_t left = wgs; left > 0; left -= slots) {
                 const int64_t now = left < slots ? left : slots;
-                // workgroups spread over the CUs first; a CU that streams gets its share of the HBM rate
-                const double active = now < num_cus ? (double)now : (double)num_cus;
-                const double f = active / num_cus;
-                t += kRound + per_wg * now / (kRate * f);
+                const double per_tile = tile_bytes * now / kRate;  // all workgroups of the round share the stream
+                t += kRound + tiles_per_wg * (per_tile > kTile ? per_tile : kTile) +
+                     now * (kWg + (s > 1 ? part_bytes / kPartRate : 0.0));
             }
-            if (t < best * 0.98) { best = t; splits = s; }  // prefer fewer splits unless clearly better
+            cost[s] = t;
+            if (t < best) best = t;
         }
+        splits = 1;
+        while (cost[splits] > best * 1.01) ++splits;  // the fewest splits within 1 % of the best estimate
     }
     int chunk = (max_seq_len + splits - 1) / splits;
     chunk = ((chunk + 31) / 32) * 32;
@@ -878,8 +887,11 @@ template <int D, int W, int BALANCED>
 static hipError_t launch_variant(const AttnArgs &a, const AttnPlan &plan, hipStream_t stream, AttnLaunchEvents *ev)
 {
     auto kern = attn_split_kernel<D, W, kStages, 0, BALANCED>;
-    auto comb = (!BALANCED && plan.num_splits > 8) ? attn_combine_kernel<D, W, BALANCED, 16>
-                                                   : attn_combine_kernel<D, W, BALANCED, 8>;
+    auto comb = attn_combine_kernel<D, W, BALANCED, 8>;
+    if constexpr (!BALANCED) {
+        if (plan.num_splits > 16) comb = attn_combine_kernel<D, W, 0, 32>;
+        else if (plan.num_splits > 8) comb = attn_combine_kernel<D, W, 0, 16>;
+    }
     const bool timed = ev && ev->on;
     dim3 grid(BALANCED ? (unsigned)plan.bal_wgs
                        : (unsigned)plan.num_splits * (unsigned)a.num_kv_heads * (unsigned)a.batch);
