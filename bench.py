@@ -88,6 +88,9 @@ def parse():
     ap.add_argument("--kernel-steps", type=int, default=48,
                     help="whole steps run after the timed region with HIP events attached to the attention "
                          "kernels (two attention calls each; 0: no kernel timing, no roofline)")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="the timed region is run this many times in all, each from the same cache lengths (the "
+                         "first is `value`; all of them and their median go to detail.repeats); 1 = no repeat")
     ap.add_argument("--kernel-every", type=int, default=1,
                     help="attach the events to every Nth of those steps only")
     ap.add_argument("--ceiling-launches", type=int, default=50,
@@ -524,6 +527,7 @@ def main():
         run_step(i)
     torch.cuda.synchronize()
     lens_before = seq_lens.cpu().numpy().astype(np.int64)
+    lens_start_dev = seq_lens.clone()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record(stream)
@@ -548,6 +552,23 @@ def main():
         torch.cuda.synchronize()
         samples = step.attn_timing_samples()
     lens_post = seq_lens.cpu().numpy().astype(np.int64)
+
+    # ---- repeats of the timed region: the lengths go back to where the region started (the commits then
+    # rewrite the same rows), the same K steps run again; `value` stays the first region's
+    region_ms = [total_ms / args.steps]
+    lens_post_dev = seq_lens.clone()
+    for _ in range(max(args.repeats, 1) - 1):
+        seq_lens.copy_(lens_start_dev)
+        torch.cuda.synchronize()
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        r0.record(stream)
+        for i in range(args.steps):
+            run_step(args.warmup + i)
+        r1.record(stream)
+        torch.cuda.synchronize()
+        region_ms.append(r0.elapsed_time(r1) / args.steps)
+    seq_lens.copy_(lens_post_dev)  # back to the state the blocks below describe (the rows up to there are in place)
+    torch.cuda.synchronize()
     err = step.device_error()
     if err != 0:
         log("bench.py: device error word %d after the timed region" % err)
@@ -640,6 +661,11 @@ def main():
     extra["prewarm"] = "%d untimed attention-only steps over %.0f ms before the warm-up steps (clock settling)" % (
         n_pre, args.prewarm_ms)
     extra["pools"] = n_pools
+    extra["repeats"] = {"ms_per_step": [round(x, 5) for x in region_ms],
+                        "median_ms_per_step": round(float(np.median(region_ms)), 5),
+                        "median_steps_per_s": round(1000.0 / float(np.median(region_ms)), 2),
+                        "what": "the same %d steps from the same cache lengths, %d times; the first is `value`" % (
+                            args.steps, len(region_ms))}
 
     out = {
         "metric": "draft+verify block-attn steps/s and achieved KV-read HBM TB/s (1 MI355X)",
