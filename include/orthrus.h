@@ -52,13 +52,13 @@ typedef enum {
 
 /*
  * num_splits value that asks for the balanced partition.  A fixed split count cuts every
- * sequence at the same token positions, sized by the host bound max_seq_len: when the lengths
- * of a batch differ widely (the host cannot see them), most workgroups end early and the call
- * lasts as long as the longest sequence's pieces.  The balanced partition instead reads the
- * lengths on the device and gives every resident workgroup the same number of 32-token tiles,
- * cutting sequences wherever the shares end; results are merged exactly as with fixed splits
- * and are equally deterministic.  Meant for batches with ragged lengths; with equal lengths a
- * fixed split count is as fast or faster.
+ * sequence into the same number of pieces (each sequence by its own length, read on the device;
+ * the host bound max_seq_len only sizes the grid): when the lengths of a batch differ widely,
+ * the pieces of short sequences end early and the call lasts as long as the longest sequence's
+ * pieces.  The balanced partition instead gives every resident workgroup the same number of
+ * 32-token tiles, cutting sequences wherever the shares end; results are merged exactly as with
+ * fixed splits and are equally deterministic.  Meant for batches with ragged lengths; with equal
+ * lengths a fixed split count is as fast or faster.
  */
 #define ORTHRUS_SPLITS_BALANCED (-1)
 

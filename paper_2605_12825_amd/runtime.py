@@ -70,6 +70,11 @@ class DecodeStep:
         """
         self.params.max_seq_len = int(bound)
         self.num_splits = B.orthrus_attn_num_splits_on(self.ctx, self.params)
+        # the constructor sized the workspace for the bounds min_seq_len_bound + i * block_k; any other bound
+        # whose plan needs more gets a larger one here (rare, and never inside a captured sequence)
+        n = B.orthrus_attn_workspace_bytes_on(self.ctx, self.params)
+        if n > self.attn_ws.numel():
+            self.attn_ws = torch.empty(n, dtype=torch.uint8, device=self.device)
 
     def close(self):
         if self.ctx:
