@@ -3,7 +3,8 @@ batch, page size, paging layout, ragged lengths (empty sequences included), spli
 all drawn per case, so that combinations nobody wrote down by hand get run too (compute-wave counts
 1..8, ragged last tiles, in-block tiles shorter than 32, the three merge forms, the balanced partition).
 Then whole decode steps on random shapes: both attention views, the greedy consensus and the commit,
-with tokens, lengths and pool bytes bit-exact.  Same bars as every other parity test.
+with tokens, lengths and pool bytes bit-exact; the AR prefill and the temperature > 0 consensus on random
+shapes.  Same bars as every other parity test.
 """
 import numpy as np
 import pytest
@@ -84,3 +85,68 @@ def test_decode_steps_on_a_random_shape(case_id):
         _gathered_equal(case, ref)  # the oracle appended into `ref` in place: lengths and every pool byte agree
     assert case.step.device_error() == 0, what
     case.step.close()
+
+
+@pytest.mark.parametrize("case_id", range(12))
+def test_prefill_on_a_random_shape(case_id):
+    """AR prefill (Section 3.1): random head shapes, ragged cache lengths and ragged new-token counts."""
+    from test_gpu_prefill import Case, _check, _new_tokens
+    rng = np.random.default_rng(7500 + case_id)
+    d = int(rng.choice([64, 128]))
+    hkv = int(rng.integers(1, 4))
+    g = int(rng.integers(1, 9))           # 32 new tokens x g query heads per work item: every wave count 1..8
+    batch = int(rng.integers(1, 5))
+    page = int(rng.choice([16, 32, 64]))
+    hi = int(rng.choice([0, 50, 300]))
+    T = int(rng.choice([1, 31, 33, 70, 150]))
+    lens = rng.integers(0, hi + 1, size=batch).astype(np.int32)
+    new_lens = rng.integers(0, T + 1, size=batch).astype(np.int32)
+    new_lens[int(rng.integers(0, batch))] = T
+    paging = str(rng.choice(["contiguous", "shuffled", "scattered"]))
+    w = Workload(name="rnd_pf", seed=7500 + case_id, batch=batch, num_q_heads=g * hkv, num_kv_heads=hkv, head_dim=d,
+                 block_k=8, context=hi, page_size=page, paging=paging, steps=(T + 7) // 8 + 1)
+    cache = make_cache(w, seq_lens=lens)
+    q, kn, vn = _new_tokens(w, T, 9700 + case_id)
+    ref_k, ref_v, ref_l = cache["k_pool"].copy(), cache["v_pool"].copy(), cache["seq_lens"].copy()
+    want, _ = oracle.prefill_attn(w.sm_scale, q, kn, vn, new_lens, ref_k, ref_v, cache["page_table"], ref_l)
+    case = Case(w, cache, max_seq_len=min(int(lens.max()) + T, cache["page_table"].shape[1] * page))
+    got = case.prefill(q, kn, vn, new_lens)
+    _check(got, want, new_lens)
+    k, v, l = case.state()
+    np.testing.assert_array_equal(l, ref_l)
+    np.testing.assert_array_equal(k, ref_k)
+    np.testing.assert_array_equal(v, ref_v)
+    assert case.step.device_error() == 0
+    case.step.close()
+
+
+@pytest.mark.parametrize("case_id", range(8))
+def test_sampling_consensus_on_a_random_shape(case_id):
+    """Temperature > 0 consensus + commit on random shapes; cases whose decisions sit within fp32 rounding of
+    flipping are replaced by the next seed (the oracle reports the margins)."""
+    from test_gpu_sampling import _clear_case, _run, _same
+    rng = np.random.default_rng(7700 + case_id)
+    d = int(rng.choice([64, 128]))
+    hkv = int(rng.integers(1, 4))
+    kblk = int(rng.integers(1, 17))
+    batch = int(rng.integers(1, 7))
+    page = int(rng.choice([16, 32]))
+    vocab = int(rng.choice([97, 1000, 8193, 20011]))
+    temperature = float(rng.choice([0.6, 1.0, 1.4]))
+    divergence = float(rng.choice([0.2, 0.5, 1.0]))
+    lens = rng.integers(0, 120, size=batch).astype(np.int32)
+    w = Workload(name="rnd_smp", seed=7700 + case_id, batch=batch, num_q_heads=2 * hkv, num_kv_heads=hkv, head_dim=d,
+                 block_k=kblk, context=120, page_size=page, paging="shuffled", vocab=vocab, steps=1)
+    c, _ = _clear_case(w, 9900 + 50 * case_id, temperature=temperature, divergence=divergence)
+    cache = make_cache(w, seq_lens=lens)
+    blk = make_block(w, 9800 + case_id)
+    rk, rv, rl = cache["k_pool"].copy(), cache["v_pool"].copy(), cache["seq_lens"].copy()
+    want = oracle.sampling_consensus_commit(c["ar_logits"], c["diff_logits"], c["draft_tokens"], c["accept_u"],
+                                            c["gumbel"], temperature, blk["k_blk"], blk["v_blk"], rk, rv,
+                                            cache["page_table"], rl)
+    got = _run(w, cache, c, blk)
+    _same(got, want)
+    assert got["err"] == 0
+    np.testing.assert_array_equal(got["seq_lens"], rl)
+    np.testing.assert_array_equal(got["k_pool"], rk)
+    np.testing.assert_array_equal(got["v_pool"], rv)
