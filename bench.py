@@ -618,6 +618,9 @@ def main():
         extra["attn_combine_kernel_us"] = stats(cb)["avg_us"]
         extra["attn_call_kernels_us"] = stats(call)["avg_us"]
         extra["attn_call_frac_of_peak"] = r_call["frac"]
+        if len(call) >= 2:  # calls alternate: diffusion view (follows the previous step's commit), AR view
+            extra["attn_call_us_by_view"] = {"diffusion": round(float(call[0::2].mean()), 2),
+                                             "ar_verify": round(float(call[1::2].mean()), 2)}
         # ---- measured ceiling of the access pattern: the same bytes through the same page table, no arithmetic
         step.attn_timing(True)
         for j in range(args.ceiling_launches):
