@@ -13,10 +13,12 @@
 //            one loader wave.  Every compute wave reads every K/V tile, so the tile stream is shared:
 //            the loader sends 32-token tiles from global memory straight into an NS-stage LDS ring
 //            (global_load_lds_dwordx4: coalesced 16-byte loads, one 256-byte row per 16 lanes), NS-1
-//            tiles ahead of the one being computed, with one workgroup barrier per tile.  The launch
-//            plan aims at one workgroup per CU: that keeps ~32 KB in flight per CU, which already
-//            saturates HBM, and shares the bandwidth evenly between the XCDs (with twice as much in
-//            flight some XCDs finish 20 % later than others).
+//            tiles ahead of the one being computed, with one workgroup barrier per tile.  For a
+//            launch that can fill the chip the plan lands on one workgroup per CU: that keeps ~32 KB
+//            in flight per CU, which already saturates HBM, and shares the bandwidth evenly between
+//            the XCDs (with twice as much in flight some XCDs finish 20 % later than others); a
+//            smaller launch trades the length of a workgroup's tile chain against the cost of more
+//            pieces (plan_attn).
 //   MFMA   = v_mfma_f32_32x32x16_bf16 for both contractions, on the transposed problem:
 //            S^T[token][row] = K_tile . Q^T   (A = K from LDS, B = Q held in registers)
 //            O^T[d][row]    += V^T . P^T      (A = V through the LDS transpose read, B = P)
@@ -31,7 +33,7 @@
 //            both are described at the kernel.
 //   caches = K/V tiles are read once per call.  When the model streams more K/V between two passes
 //            over the same cache than the last-level cache holds, the tile loads carry the
-//            non-temporal hint; the fp32 partials always leave with non-temporal stores.
+//            non-temporal hint and the fp32 partials leave with non-temporal stores.
 #include "orthrus_internal.h"
 
 #include <hip/hip_ext.h>
