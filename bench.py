@@ -103,6 +103,8 @@ def parse():
     ap.add_argument("--calibrate-read", action="store_true",
                     help="only time the no-arithmetic K/V stream probe on the workload's cache (the measured "
                          "ceiling of the paged read pattern) and print it")
+    ap.add_argument("--calibrate-after-steps", type=int, default=0,
+                    help="with --calibrate-read: run this many whole steps first (ragged, grown lengths)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (known traffic, used to "
                          "scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -506,13 +508,16 @@ def main():
         pre_i[0] += 1
     n_pre = settle_clocks(torch, args.prewarm_ms, pre_one)
     if args.calibrate_read:
+        for i in range(args.calibrate_after_steps):   # optionally from the state that many whole steps reach
+            run_step(i)
+        torch.cuda.synchronize()
         step.attn_timing(True)
         for j in range(max(args.ceiling_launches, 1)):
             step.kv_stream_probe(k_pools[j % n_pools], v_pools[j % n_pools], page_table, seq_lens)
         step.attn_timing(False)
         torch.cuda.synchronize()
         pr = np.array([x[0] for x in step.attn_timing_samples()])
-        nbytes = float(cache["seq_lens"].astype(np.int64).sum()) * w.num_kv_heads * 2 * w.head_dim * 2
+        nbytes = float(seq_lens.cpu().numpy().astype(np.int64).sum()) * w.num_kv_heads * 2 * w.head_dim * 2
         print(json.dumps({"calibrate_read": "the attention kernel with idle compute waves: the K/V loads of one attention "
                           "call over the %s cache, no arithmetic" % w.name, "bytes_per_launch": int(nbytes),
                           "launches": int(len(pr)), "avg_us": round(float(pr.mean()), 2),

@@ -3,9 +3,9 @@
 // the block, AR verification view causal inside the block).
 //
 // Work decomposition
-//   grid   = one workgroup per (split, KV head g, sequence b).  A workgroup streams cache tokens
-//            [split*chunk_b, min(L_b, (split+1)*chunk_b)) of KV head g once (chunk_b: the sequence's own
-//            length cut into equal runs of whole tiles) and serves all R = G*K
+//   grid   = one workgroup per (split, KV head g, sequence b).  A workgroup streams its piece of the
+//            cache tokens of KV head g once (the sequence's own tiles, the in-block tile included, dealt
+//            out evenly to the splits: split_cut) and serves all R = G*K
 //            query rows that share that KV head (G query heads x K block rows).
 //            Workgroups are numbered with the sequence index fastest and the KV head slowest
 //            (consecutive ids go to different XCDs; see the kernel).
@@ -25,7 +25,7 @@
 //            In both results a lane owns one query row (lane%32), so the online-softmax row
 //            statistics are per-lane scalars and need a single cross-lane exchange (lane^32).
 //   tail   = the block's own K/V rows form one more 32-token tile, masked per view, processed by
-//            split 0.  A wave owns its rows outright, so there is no merge inside the workgroup:
+//            the unit's last piece.  A wave owns its rows outright, so there is no merge inside the workgroup:
 //            it writes final bf16 rows (one split) or an fp32 partial in register order that
 //            attn_combine_kernel merges in a fixed split order (deterministic).
 //   other forms of the same kernel: the balanced partition of a ragged batch's tiles over the
@@ -112,13 +112,25 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Cache tokens per split of a sequence of L tokens cut into `splits` runs of whole 32-token tiles
-// (at least one tile, so that the arithmetic also holds for an empty sequence).
-__host__ __device__ __forceinline__ int split_chunk(int L, int splits)
+// The tiles of one (sequence, KV head) unit, cache tiles of 32 tokens followed by the in-block tile, dealt
+// out to `splits` pieces as evenly as whole tiles allow: the first `rem` pieces get one tile more, pieces
+// past the tile count get nothing, and the in-block tile (the unit's last) lands in the last piece that
+// has any.  A launch ends with its longest piece and the others cannot make up for it (a lone CU streams
+// no faster when its neighbours are done), so one tile of imbalance costs a whole tile's time.
+struct SplitCut {
+    int first;  // first tile of the piece (tile index in the unit)
+    int count;  // tiles in it, the in-block tile included if it is the unit's last piece
+    int live;   // pieces of this unit that have any tile
+};
+__host__ __device__ __forceinline__ SplitCut split_cut(int L, int splits, int split)
 {
-    const int tiles = (L + 31) >> 5;
-    const int per = (tiles + splits - 1) / splits;
-    return (per > 0 ? per : 1) * 32;
+    const int total = ((L + 31) >> 5) + 1;  // cache tiles + the in-block tile
+    const int per = total / splits, rem = total - per * splits;
+    SplitCut c;
+    c.first = split * per + (split < rem ? split : rem);
+    c.count = per + (split < rem ? 1 : 0);
+    c.live = total < splits ? total : splits;
+    return c;
 }
 
 template <int D>
@@ -306,15 +318,15 @@ __global__ void __launch_bounds__(64 * (W + 1), 3) attn_split_kernel(const AttnA
                 final_out = true;
             } else {
                 const int L = seq_len(b);
-                // The sequence's own length, not the host's bound on it, is cut into num_splits runs of
-                // whole tiles: the pieces of a sequence stay equal however loose the bound is (it only
-                // sized the grid), e.g. when a decode loop bumps it by K per step without reading back.
-                const int chunk = split_chunk(L, a.num_splits);
-                t_begin = split * chunk;
-                if (split > 0 && t_begin >= L) return false;  // nothing of this sequence falls in the split
-                t_end = min(L, t_begin + chunk);
-                n_cache = t_end > t_begin ? (t_end - t_begin + 31) >> 5 : 0;
-                n_tiles = n_cache + (split == 0 ? 1 : 0);  // split 0 ends with the in-block tile
+                // The sequence's own length, not the host's bound on it, is cut into num_splits pieces:
+                // they stay equal however loose the bound is (it only sized the grid), e.g. when a
+                // decode loop bumps it by K per step without reading back.
+                const SplitCut cut = split_cut(L, a.num_splits, split);
+                if (cut.count == 0) return false;  // fewer tiles than splits: nothing falls in this one
+                n_tiles = __builtin_amdgcn_readfirstlane(cut.count);
+                n_cache = split == cut.live - 1 ? n_tiles - 1 : n_tiles;  // the last piece ends with the in-block tile
+                t_begin = __builtin_amdgcn_readfirstlane(cut.first * 32);
+                t_end = min(L, t_begin + n_cache * 32);
                 final_out = a.num_splits == 1;
                 part_slot = ((size_t)b * a.num_kv_heads + g) * a.num_splits + split;
             }
@@ -723,9 +735,7 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs a)
     } else {
         int L = ((const const_i32 *)a.seq_lens)[b];
         L = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
-        const int chunk = split_chunk(L, a.num_splits);  // the split kernel's cut of this sequence
-        live = (L + chunk - 1) / chunk;
-        live = live < 1 ? 1 : (live > a.num_splits ? a.num_splits : live);
+        live = split_cut(L, a.num_splits, 0).live;  // the split kernel's pieces of this sequence
         first_slot = rest_slot = (size_t)unit * a.num_splits;
         slot_step = 1;
     }
